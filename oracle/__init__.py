@@ -1,0 +1,5 @@
+"""CPU oracle for the Book-Keeping clipped-gradient path (test infrastructure only).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+package.  It shares no code with the HIP library and never imports it.
+"""
