@@ -1,0 +1,179 @@
+/*
+ * dp_bk.h -- C ABI of the Book-Keeping (BK) per-sample clipped-gradient path for
+ * linear layers on AMD MI355X (gfx950).
+ *
+ * The path is the "DP back-propagation" of the paper's section 3 for one
+ * micro-batch on one worker, before any ZeRO communication:
+ *
+ *     per-layer, per-sample squared gradient norms   (appendix A.1, mixed ghost norm)
+ *  -> sum over layers, clip factor C_i               (section 2.1, eq. (1), M = 1 group)
+ *  -> clipped weighted gradient  a^T diag(C) g       (section 3, "DP gradient")
+ *  -> + sigma * R * N(0, I) on a contiguous shard    (eq. (1); ZeRO gradient partition, section 2.2)
+ *
+ * Notation (section 3): layer input a [B, T, d_in], output gradient g = dL/ds
+ * [B, T, d_out], weight gradient [d_in, d_out]; B samples, T tokens per sample.
+ *
+ * General conventions
+ *  - Every data pointer is a DEVICE pointer unless marked "host".  The library
+ *    never dereferences a device pointer on the host.
+ *  - Tensors are dense and row-major with the last index contiguous.  bf16
+ *    tensors must be 16-byte aligned, fp32 tensors 16-byte aligned.
+ *  - The caller owns every buffer.  The library allocates no device memory,
+ *    keeps no mutable global state and never synchronises: work is enqueued on
+ *    `stream` (a hipStream_t passed as void*; NULL is the default stream) and the
+ *    call returns at once.  Calls on one stream execute in order.
+ *  - Results are deterministic: no floating-point atomics are used, so the same
+ *    inputs give the same bits on every run.
+ *  - Errors are return codes.  Arguments are validated on the host before
+ *    anything is launched (DP_ERR_INVALID_ARG, DP_ERR_WORKSPACE); a failed
+ *    launch gives DP_ERR_HIP.  On any error nothing has been enqueued.
+ */
+#ifndef DP_BK_H
+#define DP_BK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DP_OK = 0,
+  DP_ERR_INVALID_ARG = 1,  /* NULL pointer, non-positive size, bad enum, misalignment, bad R/sigma */
+  DP_ERR_UNSUPPORTED = 2,  /* valid request this build has no kernel for */
+  DP_ERR_WORKSPACE = 3,    /* workspace missing or smaller than dp_norm_workspace_bytes() */
+  DP_ERR_HIP = 4           /* the HIP runtime refused a launch */
+} dp_status;
+
+typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;             /* storage type of a and g */
+typedef enum { DP_CLIP_STANDARD = 0, DP_CLIP_AUTOMATIC = 1 } dp_clip_mode;
+typedef enum { DP_PATH_GHOST = 0, DP_PATH_PEREX = 1 } dp_path;
+
+/* One linear layer's book-kept tensors (appendix A.2: activations and output gradients of
+ * every layer stay resident until the clip factors are known). */
+typedef struct {
+  const void* a;   /* device, [B, T, d_in]  */
+  const void* g;   /* device, [B, T, d_out] */
+  int32_t T;       /* tokens per sample at this layer */
+  int32_t d_in;
+  int32_t d_out;
+  int32_t path;    /* dp_path used for this layer's norm (ignored by dp_clipped_grad_multi) */
+} dp_layer;
+
+const char* dp_status_string(dp_status s);
+
+/* Library/ABI version: major*10000 + minor*100 + patch. */
+int dp_version(void);
+
+/*
+ * Mixed ghost norm selection (appendix A.1: "the cheaper of two techniques at each layer").
+ * Pure host function.  Rule: ghost norm iff 2*T^2 <= d_in*d_out (the two T x T Gram
+ * matrices take no more room than one instantiated d_in x d_out gradient); ties go to
+ * the ghost norm.  Returns DP_PATH_GHOST for non-positive arguments.
+ */
+dp_path dp_choose_path(int64_t T, int64_t d_in, int64_t d_out);
+
+/*
+ * Bytes of device workspace that dp_ghost_norm / dp_perex_norm need for one layer
+ * (per-workgroup partial sums that are then added in a fixed order).  Returns 0 for
+ * invalid arguments.
+ */
+size_t dp_norm_workspace_bytes(dp_path path, dp_dtype dt, int B, int T, int d_in, int d_out);
+
+/*
+ * Ghost norm (appendix A.1, eq. "mixed ghost norm", right-hand side):
+ *   sqnorm_out[i] = sum_{t,t'} (a[i,t,:] . a[i,t',:]) * (g[i,t,:] . g[i,t',:]),   i < B.
+ * The two T x T Gram matrices are never written to memory.  bf16 inputs are multiplied
+ * exactly and accumulated in fp32.
+ *   a, g        device inputs, [B,T,d_in] and [B,T,d_out] of type dt
+ *   sqnorm_out  device, [B] fp32, overwritten
+ *   ws          device scratch of at least dp_norm_workspace_bytes(DP_PATH_GHOST, ...) bytes,
+ *               16-byte aligned; contents undefined afterwards
+ * bf16 requires d_in and d_out to be multiples of 8 (16-byte rows).
+ */
+dp_status dp_ghost_norm(const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
+                        int d_out, float* sqnorm_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Per-sample gradient instantiation norm (appendix A.1, left-hand side):
+ *   sqnorm_out[i] = || a[i]^T g[i] ||_F^2,   a[i]^T g[i] in R^{d_in x d_out}.
+ * The per-sample gradients live only in accumulator registers.  Same arguments,
+ * alignment rules and workspace protocol as dp_ghost_norm (with DP_PATH_PEREX).
+ */
+dp_status dp_perex_norm(const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
+                        int d_out, float* sqnorm_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Cross-layer accumulation and clip factor (section 2.1; all-layer clipping, one group):
+ *   norm_i = sqrt(max(0, sum_l sqnorm[l*B + i]))            (layers added in index order)
+ *   DP_CLIP_STANDARD :  C_i = min(R / norm_i, 1)            (norm_i = 0 gives C_i = 1)
+ *   DP_CLIP_AUTOMATIC:  C_i = R / (norm_i + stability)      (the paper prints R = 1, stability 0.01)
+ *   sqnorm    device, [L, B] fp32 row-major
+ *   C_out     device, [B] fp32
+ *   norm_out  device, [B] fp32, or NULL
+ * R must be > 0 (+infinity allowed: standard clipping then gives C = 1); stability >= 0.
+ * Layer-wise clipping is this call with L = 1 per layer.
+ */
+dp_status dp_clip_factors(const float* sqnorm, int L, int B, dp_clip_mode mode, float R,
+                          float stability, float* C_out, float* norm_out, void* stream);
+
+/*
+ * Clip-weighted gradient (section 3, "DP gradient" without the noise term):
+ *   grad[j, k] (+)= sum_i C[i] * sum_t a[i,t,j] * g[i,t,k],   j < d_in, k < d_out.
+ * C[i] is applied in fp32 to sample i's exact partial product, never to the bf16 inputs.
+ *   C           device, [B] fp32
+ *   grad        device, [d_in, d_out] fp32 row-major
+ *   accumulate  0: overwrite grad; 1: add to it (gradient accumulation over micro-batches)
+ * bf16 requires d_in and d_out to be multiples of 8.
+ */
+dp_status dp_clipped_grad(const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
+                          int d_out, const float* C, float* grad, int accumulate, void* stream);
+
+/*
+ * Gaussian mechanism on one rank's contiguous gradient shard (eq. (1) with one group):
+ *   grad_slice[e - global_offset] += sigma * R * z_e,   e in [global_offset, global_offset+count)
+ * z_e ~ N(0,1) is a pure function of (seed, step, e): Philox4x32-10 block k = e >> 2 with
+ * counter (k_lo, k_hi, step_lo, step_hi) and key (seed_lo, seed_hi) gives (x0,x1,x2,x3);
+ * u = ((x >> 9) + 0.5) * 2^-23; (z_{4k}, z_{4k+1}) = sqrt(-2 ln u(x0)) * (cos, sin)(2 pi u(x1)),
+ * (z_{4k+2}, z_{4k+3}) likewise from (x2, x3).  Any sharding of the flattened gradient
+ * therefore draws the same noise.  A (seed, step) pair must not be reused.
+ *   grad_slice     device, fp32, points at element global_offset; 4-byte aligned
+ *   sigma          noise multiplier, >= 0; sigma == 0 enqueues nothing (R may be +inf then)
+ *   R              clipping threshold, > 0 and finite when sigma > 0
+ */
+dp_status dp_add_noise(float* grad_slice, uint64_t global_offset, uint64_t count, float sigma,
+                       float R, uint64_t seed, uint64_t step, void* stream);
+
+/*
+ * Raw generator stream, for verification: out[4*j .. 4*j+3] = Philox4x32-10 output of block
+ * first_block + j under the counter/key layout documented at dp_add_noise.
+ *   out  device, uint32 [4*n_blocks], 16-byte aligned
+ */
+dp_status dp_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_blocks, uint64_t seed,
+                           uint64_t step, void* stream);
+
+/*
+ * Grouped forms over a stack of layers: one launch covers every layer, so small layers
+ * (GPT-2-sized: tens of tiles each) still fill the 256 compute units.  Semantics are exactly
+ * L calls of the per-layer function.
+ *
+ * dp_norms_multi: sqnorm_out[l*B + i] for every layer l, by layers[l].path.
+ *   layers    HOST array of L descriptors (copied before the call returns)
+ *   ws        device scratch, >= dp_norms_multi_workspace_bytes(...), 16-byte aligned
+ *             (fp32 layers need none: ws may be NULL when dt == DP_F32)
+ * dp_clipped_grad_multi: grads[l] as dp_clipped_grad for every layer.
+ *   grads     HOST array of L device pointers, grads[l] -> [d_in_l, d_out_l] fp32, 16-byte aligned
+ * Layer descriptors travel in kernel arguments (at most 48 layers per launch; longer stacks
+ * take several launches), so both calls are safe under stream capture.
+ */
+size_t dp_norms_multi_workspace_bytes(const dp_layer* layers, int L, dp_dtype dt, int B);
+dp_status dp_norms_multi(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out,
+                         void* ws, size_t ws_bytes, void* stream);
+dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                float* const* grads, int accumulate, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DP_BK_H */

@@ -1,0 +1,271 @@
+// Host side of the C ABI: argument validation, grouping of layers into launches.
+// No device code lives here and no device memory is allocated.
+#include <math.h>
+#include <vector>
+
+#include "dp_internal.h"
+
+using namespace dpbk;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool dims_ok(dp_dtype dt, int B, int T, int d, int p) {
+  if (B <= 0 || T <= 0 || d <= 0 || p <= 0) return false;
+  if (dt == DP_BF16 && ((d & 7) || (p & 7))) return false;
+  // index arithmetic inside the kernels is 64-bit for element offsets, 32-bit per dimension
+  if ((int64_t)B * T > INT32_MAX) return false;
+  return true;
+}
+
+dp_status check_layer_ptrs(const void* a, const void* g) {
+  if (!a || !g) return DP_ERR_INVALID_ARG;
+  if (!aligned16(a) || !aligned16(g)) return DP_ERR_INVALID_ARG;
+  return DP_OK;
+}
+
+int tiles_per_sample(int path, const dp_layer& ly) {
+  return path == DP_PATH_GHOST ? ghost_tiles_per_sample(ly.T) : perex_tiles_per_sample(ly.d_in, ly.d_out);
+}
+
+// Launches the norm kernels of one path for the listed layers, in chunks of kMaxGroup.
+// part_begin[l] is the layer's first slot in the partial-sum workspace.
+dp_status run_norm_path(int path, const dp_layer* layers, const std::vector<int>& which,
+                        const std::vector<int64_t>& part_begin, int B, float* partials,
+                        float* sqnorm_out, hipStream_t s) {
+  for (size_t begin = 0; begin < which.size(); begin += kMaxGroup) {
+    GroupArgs ga;
+    ga.B = B;
+    ga.accumulate = 0;
+    ga.n_layers = (int)std::min<size_t>(kMaxGroup, which.size() - begin);
+    int64_t blocks = 0;
+    for (int j = 0; j < ga.n_layers; ++j) {
+      const int l = which[begin + j];
+      GroupLayer& gl = ga.layer[j];
+      gl.a = layers[l].a;
+      gl.g = layers[l].g;
+      gl.out = nullptr;
+      gl.T = layers[l].T;
+      gl.d_in = layers[l].d_in;
+      gl.d_out = layers[l].d_out;
+      gl.path = path;
+      gl.tile_begin = (int)blocks;
+      gl.sq_index = l;
+      gl.part_begin = (int)part_begin[l];
+      gl.tiles_per_sample = tiles_per_sample(path, layers[l]);
+      blocks += (int64_t)gl.tiles_per_sample * B;
+    }
+    ga.total_blocks = (int)blocks;
+    dp_status st = path == DP_PATH_GHOST ? launch_ghost_group(ga, partials, s)
+                                         : launch_perex_group(ga, partials, s);
+    if (st != DP_OK) return st;
+    st = launch_norm_reduce_group(ga, partials, sqnorm_out, s);
+    if (st != DP_OK) return st;
+  }
+  return DP_OK;
+}
+
+// Total partial-sum slots, or -1 if a layer is invalid.
+int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, std::vector<int64_t>* begin) {
+  if (!layers || L <= 0 || B <= 0) return -1;
+  int64_t total = 0;
+  for (int l = 0; l < L; ++l) {
+    if (!dims_ok(dt, B, layers[l].T, layers[l].d_in, layers[l].d_out)) return -1;
+    if (layers[l].path != DP_PATH_GHOST && layers[l].path != DP_PATH_PEREX) return -1;
+    if (begin) begin->push_back(total);
+    if (dt == DP_BF16) total += (int64_t)tiles_per_sample(layers[l].path, layers[l]) * B;
+    if (total > INT32_MAX) return -1;
+  }
+  return total;
+}
+
+dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
+                     size_t ws_bytes, hipStream_t s) {
+  if (dt != DP_F32 && dt != DP_BF16) return DP_ERR_INVALID_ARG;
+  if (!sqnorm_out) return DP_ERR_INVALID_ARG;
+  std::vector<int64_t> begin;
+  const int64_t slots = norm_slots(layers, L, dt, B, &begin);
+  if (slots < 0) return DP_ERR_INVALID_ARG;
+  for (int l = 0; l < L; ++l) {
+    dp_status st = check_layer_ptrs(layers[l].a, layers[l].g);
+    if (st != DP_OK) return st;
+  }
+  if (dt == DP_F32) {
+    for (int l = 0; l < L; ++l) {
+      const dp_layer& ly = layers[l];
+      const float* a = static_cast<const float*>(ly.a);
+      const float* g = static_cast<const float*>(ly.g);
+      float* out = sqnorm_out + (size_t)l * B;
+      dp_status st = ly.path == DP_PATH_GHOST ? launch_ghost_f32(a, g, B, ly.T, ly.d_in, ly.d_out, out, s)
+                                              : launch_perex_f32(a, g, B, ly.T, ly.d_in, ly.d_out, out, s);
+      if (st != DP_OK) return st;
+    }
+    return DP_OK;
+  }
+  if (!ws || ws_bytes < (size_t)slots * sizeof(float)) return DP_ERR_WORKSPACE;
+  if (!aligned16(ws)) return DP_ERR_INVALID_ARG;
+  std::vector<int> ghost, perex;
+  for (int l = 0; l < L; ++l) (layers[l].path == DP_PATH_GHOST ? ghost : perex).push_back(l);
+  float* partials = static_cast<float*>(ws);
+  dp_status st = run_norm_path(DP_PATH_GHOST, layers, ghost, begin, B, partials, sqnorm_out, s);
+  if (st != DP_OK) return st;
+  return run_norm_path(DP_PATH_PEREX, layers, perex, begin, B, partials, sqnorm_out, s);
+}
+
+dp_status single_norm(dp_path path, const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
+                      int d_out, float* sqnorm_out, void* ws, size_t ws_bytes, void* stream) {
+  dp_layer ly;
+  ly.a = a;
+  ly.g = g;
+  ly.T = T;
+  ly.d_in = d_in;
+  ly.d_out = d_out;
+  ly.path = path;
+  return norms_impl(&ly, 1, dt, B, sqnorm_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dp_status_string(dp_status s) {
+  switch (s) {
+    case DP_OK: return "ok";
+    case DP_ERR_INVALID_ARG: return "invalid argument";
+    case DP_ERR_UNSUPPORTED: return "unsupported";
+    case DP_ERR_WORKSPACE: return "workspace missing or too small";
+    case DP_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int dp_version(void) { return 100; }
+
+dp_path dp_choose_path(int64_t T, int64_t d_in, int64_t d_out) {
+  if (T <= 0 || d_in <= 0 || d_out <= 0) return DP_PATH_GHOST;
+  // 2 T^2 <= d_in d_out without overflow: compare in 128 bits.
+  const __int128 lhs = (__int128)2 * T * T, rhs = (__int128)d_in * d_out;
+  return lhs <= rhs ? DP_PATH_GHOST : DP_PATH_PEREX;
+}
+
+size_t dp_norm_workspace_bytes(dp_path path, dp_dtype dt, int B, int T, int d_in, int d_out) {
+  dp_layer ly = {nullptr, nullptr, T, d_in, d_out, (int32_t)path};
+  return dp_norms_multi_workspace_bytes(&ly, 1, dt, B);
+}
+
+size_t dp_norms_multi_workspace_bytes(const dp_layer* layers, int L, dp_dtype dt, int B) {
+  if (dt != DP_F32 && dt != DP_BF16) return 0;
+  const int64_t slots = norm_slots(layers, L, dt, B, nullptr);
+  if (slots < 0) return 0;
+  // never 0 for a valid request, so "0 = invalid" stays unambiguous
+  return (size_t)(slots > 0 ? slots : 4) * sizeof(float);
+}
+
+dp_status dp_ghost_norm(const void* a, const void* g, dp_dtype dt, int B, int T, int d_in, int d_out,
+                        float* sqnorm_out, void* ws, size_t ws_bytes, void* stream) {
+  return single_norm(DP_PATH_GHOST, a, g, dt, B, T, d_in, d_out, sqnorm_out, ws, ws_bytes, stream);
+}
+
+dp_status dp_perex_norm(const void* a, const void* g, dp_dtype dt, int B, int T, int d_in, int d_out,
+                        float* sqnorm_out, void* ws, size_t ws_bytes, void* stream) {
+  return single_norm(DP_PATH_PEREX, a, g, dt, B, T, d_in, d_out, sqnorm_out, ws, ws_bytes, stream);
+}
+
+dp_status dp_norms_multi(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
+                         size_t ws_bytes, void* stream) {
+  return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_clip_factors(const float* sqnorm, int L, int B, dp_clip_mode mode, float R, float stability,
+                          float* C_out, float* norm_out, void* stream) {
+  if (!sqnorm || !C_out || L <= 0 || B <= 0) return DP_ERR_INVALID_ARG;
+  if (mode != DP_CLIP_STANDARD && mode != DP_CLIP_AUTOMATIC) return DP_ERR_INVALID_ARG;
+  if (!(R > 0.f)) return DP_ERR_INVALID_ARG;                      // rejects NaN too
+  if (!(stability >= 0.f) || isinf(stability)) return DP_ERR_INVALID_ARG;
+  return launch_clip_factors(sqnorm, L, B, (int)mode, R, stability, C_out, norm_out,
+                             static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                float* const* grads, int accumulate, void* stream) {
+  if (dt != DP_F32 && dt != DP_BF16) return DP_ERR_INVALID_ARG;
+  if (!layers || !grads || !C || L <= 0 || B <= 0) return DP_ERR_INVALID_ARG;
+  if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
+  for (int l = 0; l < L; ++l) {
+    if (!dims_ok(dt, B, layers[l].T, layers[l].d_in, layers[l].d_out)) return DP_ERR_INVALID_ARG;
+    dp_status st = check_layer_ptrs(layers[l].a, layers[l].g);
+    if (st != DP_OK) return st;
+    if (!grads[l] || !aligned16(grads[l])) return DP_ERR_INVALID_ARG;
+    if ((int64_t)clipped_grad_tiles(layers[l].d_in, layers[l].d_out) > INT32_MAX / 2) return DP_ERR_INVALID_ARG;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dt == DP_F32) {
+    for (int l = 0; l < L; ++l) {
+      dp_status st = launch_clipped_grad_f32(static_cast<const float*>(layers[l].a),
+                                             static_cast<const float*>(layers[l].g), B, layers[l].T,
+                                             layers[l].d_in, layers[l].d_out, C, grads[l], accumulate, s);
+      if (st != DP_OK) return st;
+    }
+    return DP_OK;
+  }
+  int l = 0;
+  while (l < L) {
+    GroupArgs ga;
+    ga.B = B;
+    ga.accumulate = accumulate;
+    ga.n_layers = 0;
+    int64_t blocks = 0;
+    while (l < L && ga.n_layers < kMaxGroup) {
+      const int64_t tiles = clipped_grad_tiles(layers[l].d_in, layers[l].d_out);
+      if (ga.n_layers > 0 && blocks + tiles > INT32_MAX / 2) break;
+      GroupLayer& gl = ga.layer[ga.n_layers++];
+      gl.a = layers[l].a;
+      gl.g = layers[l].g;
+      gl.out = grads[l];
+      gl.T = layers[l].T;
+      gl.d_in = layers[l].d_in;
+      gl.d_out = layers[l].d_out;
+      gl.path = 0;
+      gl.tile_begin = (int)blocks;
+      gl.sq_index = l;
+      gl.part_begin = 0;
+      gl.tiles_per_sample = (int)tiles;
+      blocks += tiles;
+      ++l;
+    }
+    ga.total_blocks = (int)blocks;
+    dp_status st = launch_clipped_grad_group(ga, C, s);
+    if (st != DP_OK) return st;
+  }
+  return DP_OK;
+}
+
+dp_status dp_clipped_grad(const void* a, const void* g, dp_dtype dt, int B, int T, int d_in, int d_out,
+                          const float* C, float* grad, int accumulate, void* stream) {
+  dp_layer ly = {a, g, T, d_in, d_out, 0};
+  float* grads[1] = {grad};
+  return dp_clipped_grad_multi(&ly, 1, dt, B, C, grads, accumulate, stream);
+}
+
+dp_status dp_add_noise(float* grad_slice, uint64_t global_offset, uint64_t count, float sigma, float R,
+                       uint64_t seed, uint64_t step, void* stream) {
+  if (!(sigma >= 0.f) || isinf(sigma)) return DP_ERR_INVALID_ARG;
+  if (!(R > 0.f)) return DP_ERR_INVALID_ARG;
+  if (global_offset + count < global_offset) return DP_ERR_INVALID_ARG;   // wraps 2^64
+  if (sigma == 0.f || count == 0) return DP_OK;                            // non-private: nothing to add
+  if (isinf(R)) return DP_ERR_INVALID_ARG;
+  if (!grad_slice || (reinterpret_cast<uintptr_t>(grad_slice) & 3u)) return DP_ERR_INVALID_ARG;
+  return launch_noise(grad_slice, global_offset, count, sigma * R, seed, step,
+                      static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_blocks, uint64_t seed,
+                           uint64_t step, void* stream) {
+  if (!out || !aligned16(out)) return DP_ERR_INVALID_ARG;
+  if (n_blocks == 0) return DP_OK;
+  if (first_block + n_blocks < first_block) return DP_ERR_INVALID_ARG;
+  return launch_philox_blocks(out, first_block, n_blocks, seed, step, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

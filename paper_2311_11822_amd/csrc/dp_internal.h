@@ -1,0 +1,68 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dp_bk.h"
+
+namespace dpbk {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+#define DP_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+// Up to this many layers travel in one launch's kernel arguments.
+constexpr int kMaxGroup = 48;
+
+// One layer of a grouped launch.  tile_begin is the first workgroup of the layer.
+struct GroupLayer {
+  const void* a;
+  const void* g;
+  float* out;       // gradient [d_in, d_out] (clipped_grad) or unused
+  int T, d_in, d_out;
+  int path;
+  int tile_begin;   // first block index that belongs to this layer
+  int sq_index;     // layer number within the caller's stack (row of sqnorm)
+  int part_begin;   // first partial-sum slot of this layer in the workspace
+  int tiles_per_sample;
+};
+
+struct GroupArgs {
+  int n_layers;
+  int total_blocks;
+  int B;
+  int accumulate;
+  GroupLayer layer[kMaxGroup];
+};
+
+inline dp_status hip_status(hipError_t e) { return e == hipSuccess ? DP_OK : DP_ERR_HIP; }
+
+// --- launchers implemented in the .hip files (all validate nothing; callers did) ---
+dp_status launch_noise(float* grad, uint64_t global_offset, uint64_t count, float stddev,
+                       uint64_t seed, uint64_t step, hipStream_t s);
+dp_status launch_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_blocks,
+                               uint64_t seed, uint64_t step, hipStream_t s);
+dp_status launch_clip_factors(const float* sqnorm, int L, int B, int mode, float R, float stability,
+                              float* C_out, float* norm_out, hipStream_t s);
+
+dp_status launch_ghost_f32(const float* a, const float* g, int B, int T, int d, int p, float* out,
+                           hipStream_t s);
+dp_status launch_perex_f32(const float* a, const float* g, int B, int T, int d, int p, float* out,
+                           hipStream_t s);
+dp_status launch_clipped_grad_f32(const float* a, const float* g, int B, int T, int d, int p,
+                                  const float* C, float* grad, int accumulate, hipStream_t s);
+
+// bf16 MFMA kernels, grouped over layers.
+int ghost_tiles_per_sample(int T);
+int perex_tiles_per_sample(int d, int p);
+int clipped_grad_tiles(int d, int p);
+dp_status launch_ghost_group(const GroupArgs& ga, float* partials, hipStream_t s);
+dp_status launch_perex_group(const GroupArgs& ga, float* partials, hipStream_t s);
+dp_status launch_norm_reduce_group(const GroupArgs& ga, const float* partials, float* sqnorm_out,
+                                   hipStream_t s);
+dp_status launch_clipped_grad_group(const GroupArgs& ga, const float* C, hipStream_t s);
+
+}  // namespace dpbk

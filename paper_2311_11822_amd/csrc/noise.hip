@@ -1,0 +1,149 @@
+// Gaussian mechanism on a contiguous gradient shard (eq. (1) of the paper, one group):
+// grad[e] += sigma*R * z_e with z_e from Philox4x32-10 (Salmon et al., SC'11) + Box-Muller.
+//
+// The pass is a stream over fp32 memory (4 B read + 4 B written per element), so the
+// kernel is built to stay under the HBM time: one thread owns one 128-bit Philox block
+// = one float4 of gradient, the round keys are wave-uniform (kernel arguments, scalar
+// registers), each 32x32->64 multiply is a single 64-bit multiply, and log2 / sin / cos
+// use the hardware units (sin and cos take their argument in revolutions, which is
+// exactly the uniform variate; measured absolute error 1.3e-7, log2 relative 1.2e-7).
+#include "dp_internal.h"
+
+namespace dpbk {
+
+namespace {
+
+constexpr uint32_t kMulA = 0xD2511F53u;
+constexpr uint32_t kMulB = 0xCD9E8D57u;
+constexpr uint32_t kWeylA = 0x9E3779B9u;
+constexpr uint32_t kWeylB = 0xBB67AE85u;
+
+struct RoundKeys {
+  uint32_t k[10][2];
+};
+
+RoundKeys make_round_keys(uint64_t seed) {
+  RoundKeys rk;
+  uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+  for (int r = 0; r < 10; ++r) {
+    rk.k[r][0] = k0;
+    rk.k[r][1] = k1;
+    k0 += kWeylA;
+    k1 += kWeylB;
+  }
+  return rk;
+}
+
+__device__ __forceinline__ void philox_block(uint64_t block, uint32_t step_lo, uint32_t step_hi,
+                                             const RoundKeys& rk, uint32_t x[4]) {
+  uint32_t c0 = (uint32_t)block, c1 = (uint32_t)(block >> 32), c2 = step_lo, c3 = step_hi;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t pa = (uint64_t)kMulA * c0;
+    const uint64_t pb = (uint64_t)kMulB * c2;
+    const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ rk.k[r][0];
+    const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ rk.k[r][1];
+    c1 = (uint32_t)pb;
+    c3 = (uint32_t)pa;
+    c0 = n0;
+    c2 = n2;
+  }
+  x[0] = c0;
+  x[1] = c1;
+  x[2] = c2;
+  x[3] = c3;
+}
+
+// u = ((x >> 9) + 1/2) * 2^-23: every step is exact in fp32.
+__device__ __forceinline__ float to_uniform(uint32_t x) {
+  return ((float)(x >> 9) + 0.5f) * 1.1920928955078125e-07f;
+}
+
+__device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float& z0, float& z1) {
+  const float ua = to_uniform(xa), ub = to_uniform(xb);
+  // -2 ln u = (-2 ln 2) log2 u
+  const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(ua));
+  z0 = r * __builtin_amdgcn_cosf(ub);
+  z1 = r * __builtin_amdgcn_sinf(ub);
+}
+
+// Blocks [first_block, first_block + n_blocks) of the element stream.  `base` points at the
+// element 4*first_block (it may lie before the caller's slice; lanes outside [lo, hi) neither
+// load nor store).  VEC: base is 16-byte aligned, so whole blocks move as float4.
+template <bool VEC>
+__global__ void __launch_bounds__(256)
+noise_kernel(float* __restrict__ base, uint64_t first_block, uint64_t n_blocks, uint64_t lo,
+             uint64_t hi, float stddev, uint32_t step_lo, uint32_t step_hi, RoundKeys rk) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n_blocks; j += stride) {
+    uint32_t x[4];
+    philox_block(first_block + j, step_lo, step_hi, rk, x);
+    float z[4];
+    box_muller(x[0], x[1], z[0], z[1]);
+    box_muller(x[2], x[3], z[2], z[3]);
+    const uint64_t e0 = 4 * j;   // element index relative to base
+    float* p = base + e0;
+    if (VEC && e0 >= lo && e0 + 4 <= hi) {
+      float4 v = *reinterpret_cast<float4*>(p);
+      v.x = fmaf(stddev, z[0], v.x);
+      v.y = fmaf(stddev, z[1], v.y);
+      v.z = fmaf(stddev, z[2], v.z);
+      v.w = fmaf(stddev, z[3], v.w);
+      *reinterpret_cast<float4*>(p) = v;
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (e0 + q >= lo && e0 + q < hi) p[q] = fmaf(stddev, z[q], p[q]);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256)
+philox_dump_kernel(uint4* __restrict__ out, uint64_t first_block, uint64_t n_blocks,
+                   uint32_t step_lo, uint32_t step_hi, RoundKeys rk) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n_blocks; j += stride) {
+    uint32_t x[4];
+    philox_block(first_block + j, step_lo, step_hi, rk, x);
+    out[j] = make_uint4(x[0], x[1], x[2], x[3]);
+  }
+}
+
+int stream_grid(uint64_t n_blocks) {
+  // 256 compute units x 8 resident workgroups; fewer when the slice is small.
+  uint64_t want = (n_blocks + 255) / 256;
+  if (want > 2048 * 4) want = 2048 * 4;
+  return want < 1 ? 1 : (int)want;
+}
+
+}  // namespace
+
+dp_status launch_noise(float* grad, uint64_t global_offset, uint64_t count, float stddev,
+                       uint64_t seed, uint64_t step, hipStream_t s) {
+  const uint64_t first_block = global_offset >> 2;
+  const uint64_t last_block = (global_offset + count - 1) >> 2;
+  const uint64_t n_blocks = last_block - first_block + 1;
+  const uint64_t lead = global_offset - 4 * first_block;   // elements of the first block before the slice
+  float* base = grad - lead;                               // never dereferenced below index `lead`
+  const bool vec = (reinterpret_cast<uintptr_t>(base) & 15u) == 0;
+  const RoundKeys rk = make_round_keys(seed);
+  const dim3 grid(stream_grid(n_blocks)), block(256);
+  if (vec)
+    hipLaunchKernelGGL(noise_kernel<true>, grid, block, 0, s, base, first_block, n_blocks, lead,
+                       lead + count, stddev, (uint32_t)step, (uint32_t)(step >> 32), rk);
+  else
+    hipLaunchKernelGGL(noise_kernel<false>, grid, block, 0, s, base, first_block, n_blocks, lead,
+                       lead + count, stddev, (uint32_t)step, (uint32_t)(step >> 32), rk);
+  return hip_status(hipGetLastError());
+}
+
+dp_status launch_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_blocks,
+                               uint64_t seed, uint64_t step, hipStream_t s) {
+  const RoundKeys rk = make_round_keys(seed);
+  hipLaunchKernelGGL(philox_dump_kernel, dim3(stream_grid(n_blocks)), dim3(256), 0, s,
+                     reinterpret_cast<uint4*>(out), first_block, n_blocks, (uint32_t)step,
+                     (uint32_t)(step >> 32), rk);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace dpbk

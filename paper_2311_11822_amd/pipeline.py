@@ -1,0 +1,60 @@
+"""Whole Book-Keeping path on one micro-batch: enqueues the library calls in order
+(paper section 3: output gradient -> clipping factor -> parameter gradient -> noising).
+Holds the buffers between calls; does no arithmetic of its own."""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+from . import binding as dp
+
+
+class BkPipeline:
+    """layers: sequence of (a, g) device tensors, a [B,T,d_in], g [B,T,d_out]; bf16 tensors may be
+    given as torch.bfloat16 or as int16/uint16 bit patterns, fp32 as torch.float32."""
+
+    def __init__(self, layers: Sequence[Tuple[torch.Tensor, torch.Tensor]], paths: Optional[List[int]] = None):
+        a0 = layers[0][0]
+        self.device = a0.device
+        self.dt = dp.DP_F32 if a0.dtype == torch.float32 else dp.DP_BF16
+        self.B = a0.shape[0]
+        self.layers = list(layers)
+        self.dims = [(a.shape[1], a.shape[2], g.shape[2]) for a, g in layers]
+        self.paths = paths if paths is not None else [dp.dp_choose_path(T, d, p) for T, d, p in self.dims]
+        self.desc = dp.layer_array([(a, g, T, d, p, path) for (a, g), (T, d, p), path
+                                    in zip(self.layers, self.dims, self.paths)])
+        L = len(layers)
+        self.L = L
+        self.psi = sum(d * p for _, d, p in self.dims)
+        self.sqnorm = torch.zeros((L, self.B), dtype=torch.float32, device=self.device)
+        self.C = torch.zeros(self.B, dtype=torch.float32, device=self.device)
+        self.norm = torch.zeros(self.B, dtype=torch.float32, device=self.device)
+        self.flat = torch.zeros(self.psi, dtype=torch.float32, device=self.device)
+        self.grads, off = [], 0
+        for _, d, p in self.dims:
+            self.grads.append(self.flat[off:off + d * p].view(d, p))
+            off += d * p
+        self.grad_ptrs = (dp.C.c_void_p * L)(*[x.data_ptr() for x in self.grads])
+        ws_bytes = dp.dp_norms_multi_workspace_bytes(self.desc, self.dt, self.B)
+        if ws_bytes == 0:
+            raise dp.DpError(dp.DP_ERR_INVALID_ARG, "dp_norms_multi_workspace_bytes")
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device)
+
+    def norms(self, stream=None):
+        dp.dp_norms_multi(self.desc, self.dt, self.B, self.sqnorm, self.ws, stream)
+
+    def clip(self, mode, R, stability=0.01, stream=None):
+        dp.dp_clip_factors(self.sqnorm, self.L, self.B, mode, R, stability, self.C, self.norm, stream)
+
+    def grad(self, accumulate=0, stream=None):
+        dp.dp_clipped_grad_multi(self.desc, self.dt, self.B, self.C, self.grad_ptrs, accumulate, stream)
+
+    def noise(self, sigma, R, seed, step, offset, count, stream=None):
+        dp.dp_add_noise(self.flat.data_ptr() + 4 * offset, offset, count, sigma, R, seed, step, stream)
+
+    def step(self, mode, R, sigma, stability, seed, step, offset, count, stream=None):
+        self.norms(stream)
+        self.clip(mode, R, stability, stream)
+        self.grad(0, stream)
+        self.noise(sigma, R, seed, step, offset, count, stream)
