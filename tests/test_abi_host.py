@@ -1,0 +1,71 @@
+"""Host-only checks of the C-ABI library (no GPU): it loads, exports every symbol the header
+declares, and its pure host functions and argument validation behave as documented."""
+import os
+import re
+
+import pytest
+
+import synth_inputs as si
+from oracle import bk_oracle as o
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dp():
+    import paper_2311_11822_amd.binding as b
+    return b
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dp_bk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(dp):
+    names = declared_functions()
+    assert {"dp_ghost_norm", "dp_perex_norm", "dp_clip_factors", "dp_clipped_grad", "dp_add_noise"} <= set(names)
+    for name in names:
+        assert hasattr(dp.lib, name), name
+    assert sorted(dp.EXPORTS) == names          # the binding covers the whole header
+
+
+def test_status_strings(dp):
+    seen = {dp.lib.dp_status_string(s) for s in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert dp.dp_version() >= 100
+
+
+def test_path_rule_matches_oracle_reading(dp):
+    for w in si.WORKLOADS.values():
+        for d, p in w.layers:
+            assert dp.dp_choose_path(w.T, d, p) == o.choose_path(w.T, d, p)
+    for T, d, p in [(8, 16, 8), (8, 16, 7), (1, 1, 2), (1, 1, 1), (3037000500, 2 ** 31, 2 ** 31), (2 ** 31, 2 ** 31, 2 ** 31)]:
+        assert dp.dp_choose_path(T, d, p) == o.choose_path(T, d, p), (T, d, p)
+
+
+def test_workspace_sizes(dp):
+    assert dp.dp_norm_workspace_bytes(0, 1, 16, 256, 768, 2304) >= 16 * 3 * 4
+    assert dp.dp_norm_workspace_bytes(0, 1, 0, 256, 768, 2304) == 0
+    assert dp.dp_norm_workspace_bytes(0, 1, 1, 256, 12, 8) == 0       # bf16 row not a multiple of 16 B
+    assert dp.dp_norm_workspace_bytes(1, 0, 4, 8, 16, 16) > 0
+    layers = [(None, None, 256, 768, 768, 0), (None, None, 256, 768, 3072, 1)]
+    both = dp.dp_norms_multi_workspace_bytes(layers, 1, 16)
+    assert both == sum(dp.dp_norm_workspace_bytes(path, 1, 16, T, d, p) for _, _, T, d, p, path in layers)
+
+
+def test_validation_refuses_before_any_launch(dp):
+    lib, INV = dp.lib, dp.DP_ERR_INVALID_ARG
+    fake = 0x1000                     # never dereferenced: every call below fails validation
+    assert lib.dp_ghost_norm(None, fake, 1, 1, 8, 8, 8, fake, fake, 64, None) == INV
+    assert lib.dp_perex_norm(fake, fake, 1, 1, 8, 8, 8, None, fake, 64, None) == INV
+    assert lib.dp_ghost_norm(fake, fake, 1, 1, 8, 8, 8, fake, None, 0, None) == dp.DP_ERR_WORKSPACE
+    assert lib.dp_clip_factors(fake, 0, 1, 0, 1.0, 0.01, fake, None, None) == INV
+    assert lib.dp_clip_factors(fake, 1, 1, 0, -1.0, 0.01, fake, None, None) == INV
+    assert lib.dp_clipped_grad(fake, fake, 1, 1, 8, 8, 8, fake, None, 0, None) == INV
+    assert lib.dp_add_noise(fake, 0, 16, float("nan"), 1.0, 0, 0, None) == INV
+    assert lib.dp_add_noise(fake, 0, 16, 0.0, float("inf"), 0, 0, None) == dp.DP_OK   # sigma = 0: no-op
+    assert lib.dp_philox_blocks(None, 0, 4, 0, 0, None) == INV
+    with pytest.raises(dp.DpError):
+        dp.dp_clip_factors(fake, 1, 1, 5, 1.0, 0.01, fake, stream=0)

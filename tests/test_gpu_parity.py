@@ -1,0 +1,402 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Tolerances (stated by the task's acceptance rule): Philox integers bit-exact; fp32 paths 1e-5
+relative; bf16-in/fp32-accumulate 2e-3 relative on norms and 1e-2 relative Frobenius on gradients
+(measured before noise); normals |z_gpu - z_ref| <= 1e-5 max(1, |z_ref|).
+"""
+import math
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import bk_oracle as o
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL_F32 = 1e-5
+TOL_BF16_NORM = 2e-3
+TOL_BF16_GRAD = 1e-2
+TOL_Z = 1e-5
+
+
+@pytest.fixture(scope="module")
+def dp():
+    import paper_2311_11822_amd.binding as b
+    return b
+
+
+@pytest.fixture(scope="module")
+def Pipe():
+    from paper_2311_11822_amd.pipeline import BkPipeline
+    return BkPipeline
+
+
+def dev(x: np.ndarray):
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda()
+    return torch.from_numpy(x).cuda()
+
+
+def host(t) -> np.ndarray:
+    torch.cuda.synchronize()
+    return t.detach().cpu().numpy()
+
+
+def rel(got, want):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    return np.max(np.abs(got - want) / np.maximum(np.abs(want), 1e-300))
+
+
+def frob(got, want):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    return np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)
+
+
+def gen(w):
+    return [si.gen_layer(w, l) for l in range(w.L)]
+
+
+# ----------------------------------------------------------------------------
+# noise generator
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed,step,first,n", [
+    (1, 0, 0, 100000),
+    (0, 0, 0, 1),
+    (0xDEADBEEFCAFEF00D, 7, 12345, 4099),
+    (3, (1 << 40) + 5, (1 << 32) - 1000, 2000),       # block index crosses 2^32
+    (2 ** 64 - 1, 2 ** 64 - 1, 2 ** 40 + 1, 513),
+])
+def test_philox_stream_bit_exact(dp, seed, step, first, n):
+    out = torch.zeros(4 * n, dtype=torch.int32, device="cuda")
+    dp.dp_philox_blocks(out, first, n, seed, step)
+    got = host(out).view(np.uint32).reshape(n, 4)
+    np.testing.assert_array_equal(got, o.philox_blocks(seed, step, first, n))
+
+
+@pytest.mark.parametrize("offset,count,pad", [
+    (0, 1 << 20, 0), (0, 4, 0), (5, 1, 3), (3, 1021, 1), (1 << 34, 4096, 0), (7, 65537, 2), (1, 2, 0),
+])
+def test_normals_match_oracle_and_stay_in_slice(dp, offset, count, pad):
+    # A zero buffer with sigma*R = 1 returns z itself.  `pad` shifts the slice's address so both
+    # the float4 and the scalar kernels are exercised.
+    guard = 8
+    buf = torch.zeros(count + 2 * guard + pad, dtype=torch.float32, device="cuda")
+    view = buf[guard + pad: guard + pad + count]
+    dp.dp_add_noise(view, offset, count, 0.5, 2.0, 1, 0)
+    got = host(buf)
+    want = o.normals(1, 0, offset, count)
+    z = got[guard + pad: guard + pad + count].astype(np.float64)
+    assert np.all(np.abs(z - want) <= TOL_Z * np.maximum(1.0, np.abs(want)))
+    assert np.all(got[:guard + pad] == 0) and np.all(got[guard + pad + count:] == 0)
+
+
+def test_noise_adds_with_level_and_splits(dp):
+    n = 100003
+    base = np.random.default_rng(3).standard_normal(n).astype(np.float32)
+    one = dev(base.copy())
+    dp.dp_add_noise(one, 40, n, 0.8, 1.5, 9, 2)
+    two = dev(base.copy())
+    k = 33333
+    dp.dp_add_noise(two, 40, k, 0.8, 1.5, 9, 2)
+    dp.dp_add_noise(two.data_ptr() + 4 * k, 40 + k, n - k, 0.8, 1.5, 9, 2)
+    a, b = host(one), host(two)
+    np.testing.assert_array_equal(a, b)                  # any split draws the same noise
+    want = o.add_noise(base, 40, 0.8, 1.5, 9, 2)
+    assert np.all(np.abs(a.astype(np.float64) - want) <= 1.2 * TOL_Z * np.maximum(1.0, np.abs(want)))
+    # sigma = 0 is the non-private case: untouched, even with R = inf
+    three = dev(base.copy())
+    dp.dp_add_noise(three, 0, n, 0.0, math.inf, 9, 2)
+    np.testing.assert_array_equal(host(three), base)
+
+
+def test_noise_statistics_large(dp):
+    n = 1 << 24
+    buf = torch.zeros(n, dtype=torch.float32, device="cuda")
+    dp.dp_add_noise(buf, 0, n, 1.0, 1.0, 1, 0)
+    m, v = float(buf.double().mean()), float(buf.double().var())
+    assert abs(m) < 5 / math.sqrt(n) and abs(v - 1) < 5 * math.sqrt(2 / n)
+    assert float(buf.abs().max()) <= 5.78
+
+
+# ----------------------------------------------------------------------------
+# clip factors
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("L,B", [(1, 1), (5, 9), (144, 16), (3, 700)])
+def test_clip_factors(dp, mode, L, B):
+    rng = np.random.default_rng(L * 1000 + B)
+    sqn = rng.uniform(0, 4.0 / L, size=(L, B)).astype(np.float32)
+    sqn[:, 0] = 0.0
+    if B > 2:
+        sqn[:, 1] = 1e-9
+        sqn[0, 2] = -1e-3 if L == 1 else sqn[0, 2]
+    for R in (0.7, 1.0, math.inf):
+        if mode == 1 and math.isinf(R):
+            continue
+        Cd = torch.zeros(B, dtype=torch.float32, device="cuda")
+        nd = torch.zeros(B, dtype=torch.float32, device="cuda")
+        dp.dp_clip_factors(dev(sqn), L, B, mode, R, 0.01, Cd, nd)
+        C, norm = o.clip_factors(sqn.astype(np.float64), mode, R, 0.01)
+        np.testing.assert_allclose(host(nd), norm, rtol=TOL_F32, atol=1e-30)
+        np.testing.assert_allclose(host(Cd), C, rtol=TOL_F32)
+
+
+# ----------------------------------------------------------------------------
+# fp32 kernels (cfg0 and ragged shapes)
+# ----------------------------------------------------------------------------
+
+F32_SHAPES = [(4, 8, 16, 16), (1, 1, 1, 1), (3, 5, 7, 11), (2, 37, 50, 13), (5, 17, 3, 64)]
+
+
+@pytest.mark.parametrize("B,T,d,p", F32_SHAPES)
+def test_fp32_entry_points(dp, B, T, d, p):
+    w = si.small_workload("f32", si.F32, B, T, [(d, p)])
+    a, g = si.gen_layer(w, 0)
+    a64, g64 = si.to_f64(a), si.to_f64(g)
+    ad, gd = dev(a), dev(g)
+    want = o.perex_sqnorm(a64, g64)
+    for fn in (dp.dp_ghost_norm, dp.dp_perex_norm):
+        out = torch.zeros(B, dtype=torch.float32, device="cuda")
+        fn(ad, gd, dp.DP_F32, B, T, d, p, out, None)
+        assert rel(host(out), want) <= TOL_F32
+    C = np.random.default_rng(1).uniform(0.0, 1.0, B)
+    C[0] = 0.0
+    grad = torch.full((d, p), 7.0, dtype=torch.float32, device="cuda")
+    Cd = dev(C.astype(np.float32))
+    dp.dp_clipped_grad(ad, gd, dp.DP_F32, B, T, d, p, Cd, grad, 0)
+    G = o.clipped_grad(a64, g64, C.astype(np.float32).astype(np.float64))
+    assert frob(host(grad), G) <= TOL_F32
+    dp.dp_clipped_grad(ad, gd, dp.DP_F32, B, T, d, p, Cd, grad, 1)
+    assert frob(host(grad), 2 * G) <= TOL_F32
+
+
+def test_cfg0_pipeline_both_paths(dp, Pipe):
+    w = si.WORKLOADS["cfg0"]
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    off, cnt = w.noise_range()
+    Cs = []
+    for path in (dp.DP_PATH_GHOST, dp.DP_PATH_PEREX):
+        ref = o.private_gradient(l64, w.clip_mode, w.R, w.sigma, w.stability, w.noise_seed,
+                                 w.noise_step, off, cnt, force_path=path)
+        pipe = Pipe([(dev(a), dev(g)) for a, g in layers], paths=[path])
+        pipe.norms()
+        pipe.clip(w.clip_mode, w.R, w.stability)
+        pipe.grad()
+        assert rel(host(pipe.sqnorm), ref["sqnorm"]) <= TOL_F32
+        assert rel(host(pipe.C), ref["C"]) <= TOL_F32
+        assert frob(host(pipe.grads[0]), ref["grads"][0]) <= TOL_F32
+        pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+        np.testing.assert_allclose(host(pipe.flat), ref["flat"], rtol=0, atol=2e-5)
+        Cs.append(host(pipe.C))
+    np.testing.assert_allclose(Cs[0], Cs[1], rtol=TOL_F32)
+
+
+# ----------------------------------------------------------------------------
+# bf16 matrix-core kernels: small ragged shapes spanning several tiles
+# ----------------------------------------------------------------------------
+
+BF16_SHAPES = [
+    (2, 8, 16, 16),          # far smaller than one tile
+    (3, 130, 72, 264),       # ragged T, widths not multiples of the k-step
+    (2, 300, 136, 520),      # 3 token tiles, tile edges inside d and p
+    (1, 257, 8, 8),          # minimum widths
+    (5, 64, 392, 24),
+    (2, 513, 256, 256),      # exact tile multiples plus one token
+]
+
+
+@pytest.mark.parametrize("B,T,d,p", BF16_SHAPES)
+def test_bf16_norms(dp, B, T, d, p):
+    w = si.small_workload("b", si.BF16, B, T, [(d, p)])
+    a, g = si.gen_layer(w, 0)
+    a64, g64 = si.to_f64(a), si.to_f64(g)
+    want = o.perex_sqnorm(a64, g64)
+    np.testing.assert_allclose(o.ghost_sqnorm(a64, g64), want, rtol=1e-9)
+    ad, gd = dev(a), dev(g)
+    for path, fn in ((dp.DP_PATH_GHOST, dp.dp_ghost_norm), (dp.DP_PATH_PEREX, dp.dp_perex_norm)):
+        nbytes = dp.dp_norm_workspace_bytes(path, dp.DP_BF16, B, T, d, p)
+        assert nbytes > 0
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        out = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
+        fn(ad, gd, dp.DP_BF16, B, T, d, p, out, ws)
+        assert rel(host(out), want) <= TOL_BF16_NORM, (path, host(out), want)
+        first = host(out).copy()
+        fn(ad, gd, dp.DP_BF16, B, T, d, p, out, ws)
+        np.testing.assert_array_equal(host(out), first)       # deterministic
+
+
+@pytest.mark.parametrize("B,T,d,p", BF16_SHAPES)
+def test_bf16_clipped_grad(dp, B, T, d, p):
+    w = si.small_workload("b", si.BF16, B, T, [(d, p)])
+    a, g = si.gen_layer(w, 0)
+    a64, g64 = si.to_f64(a), si.to_f64(g)
+    C = np.random.default_rng(2).uniform(1e-3, 1.0, B).astype(np.float32)
+    if B > 2:
+        C[1] = 0.0                       # a masked sample
+        C[2] = 1.0
+    ad, gd, Cd = dev(a), dev(g), dev(C)
+    grad = torch.full((d, p), 3.0, dtype=torch.float32, device="cuda")
+    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Cd, grad, 0)
+    G = o.clipped_grad(a64, g64, C.astype(np.float64))
+    assert frob(host(grad), G) <= TOL_BF16_GRAD
+    assert frob(host(grad), G) <= 1e-5          # products are exact: only fp32 summation differs
+    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Cd, grad, 1)
+    assert frob(host(grad), 2 * G) <= 1e-5
+    # all factors zero: the gradient is zero (overwrite) and unchanged (accumulate)
+    Z = torch.zeros(B, dtype=torch.float32, device="cuda")
+    before = host(grad).copy()
+    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Z, grad, 1)
+    np.testing.assert_array_equal(host(grad), before)
+    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Z, grad, 0)
+    assert not host(grad).any()
+
+
+def test_bf16_unclipped_is_plain_product(dp):
+    # C = 1: the standard gradient a^T g over all B*T rows.
+    B, T, d, p = 3, 200, 264, 136
+    w = si.small_workload("b", si.BF16, B, T, [(d, p)])
+    a, g = si.gen_layer(w, 0)
+    ones = torch.ones(B, dtype=torch.float32, device="cuda")
+    grad = torch.zeros((d, p), dtype=torch.float32, device="cuda")
+    dp.dp_clipped_grad(dev(a), dev(g), dp.DP_BF16, B, T, d, p, ones, grad, 0)
+    want = si.to_f64(a).reshape(-1, d).T @ si.to_f64(g).reshape(-1, p)
+    assert frob(host(grad), want) <= 1e-5
+
+
+def test_multi_layer_stack_mixed_paths(dp, Pipe):
+    # A stack whose layers take different norm paths and shapes, in one grouped launch each.
+    dims = [(72, 264), (264, 72), (8, 8), (136, 136), (520, 16)]
+    w = si.small_workload("m", si.BF16, 3, 150, dims, clip_mode=si.CLIP_AUTOMATIC)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    paths = [0, 1, 1, 0, 1]
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers], paths=paths)
+    pipe.norms()
+    pipe.clip(w.clip_mode, w.R, w.stability)
+    pipe.grad()
+    want = np.stack([o.perex_sqnorm(a, g) for a, g in l64])
+    assert rel(host(pipe.sqnorm), want) <= TOL_BF16_NORM
+    C, _ = o.clip_factors(want, w.clip_mode, w.R, w.stability)
+    assert rel(host(pipe.C), C) <= TOL_BF16_NORM
+    for l, (a, g) in enumerate(l64):
+        assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, C)) <= 1e-4
+
+
+# ----------------------------------------------------------------------------
+# full-size workloads
+# ----------------------------------------------------------------------------
+
+def sampled_grad_check(w, layers, C, pipe, full_layers=(), n_samples=2048, seed=5):
+    """Gradient before noise: whole matrix for `full_layers`, else seeded random entries plus
+    the four corners' neighbourhoods, each entry computed on its own by the oracle."""
+    worst = 0.0
+    rng = np.random.default_rng(seed)
+    for l, (a, g) in enumerate(layers):
+        d, p = w.layers[l]
+        got = pipe.grads[l]
+        if l in full_layers:
+            G = o.clipped_grad(si.to_f64(a), si.to_f64(g), C)
+            worst = max(worst, frob(host(got), G))
+            continue
+        rows = np.concatenate([rng.integers(0, d, n_samples), [0, 0, d - 1, d - 1]])
+        cols = np.concatenate([rng.integers(0, p, n_samples), [0, p - 1, 0, p - 1]])
+        ur, ri = np.unique(rows, return_inverse=True)
+        uc, ci = np.unique(cols, return_inverse=True)
+        a_sel = si.to_f64(np.ascontiguousarray(a[:, :, ur]))
+        g_sel = si.to_f64(np.ascontiguousarray(g[:, :, uc]))
+        want = o.clipped_grad_entries(a_sel, g_sel, C, ri, ci)
+        idx = torch.from_numpy(rows * p + cols).cuda()
+        have = host(got.reshape(-1)[idx])
+        worst = max(worst, frob(have, want))
+    return worst
+
+
+def run_workload(dp, Pipe, name, full_layers=()):
+    w = si.WORKLOADS[name]
+    layers = gen(w)
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    # the logged path choice is the paper's rule, as the oracle reads it
+    assert pipe.paths == [o.choose_path(w.T, d, p) for d, p in w.layers]
+    pipe.norms()
+    pipe.clip(w.clip_mode, w.R, w.stability)
+    pipe.grad()
+    sqn = np.stack([
+        (o.ghost_sqnorm if path == o.PATH_GHOST else o.perex_sqnorm)(si.to_f64(a), si.to_f64(g))
+        for (a, g), path in zip(layers, pipe.paths)])
+    assert rel(host(pipe.sqnorm), sqn) <= TOL_BF16_NORM
+    C, norm = o.clip_factors(sqn, w.clip_mode, w.R, w.stability)
+    assert rel(host(pipe.norm), norm) <= TOL_BF16_NORM
+    assert rel(host(pipe.C), C) <= TOL_BF16_NORM
+    assert sampled_grad_check(w, layers, C, pipe, full_layers) <= TOL_BF16_GRAD
+    # noise on the rank's shard only; checked on the head, the tail and a window inside
+    off, cnt = w.noise_range()
+    before = pipe.flat.clone()
+    pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+    std = w.sigma * w.R
+    for lo in (off, off + cnt // 2 - 1001, off + cnt - 4096):
+        hi = min(lo + 4096, off + cnt)
+        z = (host(pipe.flat[lo:hi]).astype(np.float64) - host(before[lo:hi])) / std
+        ref = o.normals(w.noise_seed, w.noise_step, lo, hi - lo)
+        assert np.all(np.abs(z - ref) <= 2e-5 * np.maximum(1.0, np.abs(ref)))   # fp32 add of grad + noise
+    if off > 0:
+        assert torch.equal(pipe.flat[:off], before[:off])
+    if off + cnt < w.psi:
+        assert torch.equal(pipe.flat[off + cnt:], before[off + cnt:])
+        delta = (pipe.flat[off:off + cnt] - before[off:off + cnt]).double()
+        assert abs(float(delta.std()) / std - 1) < 1e-3
+    return pipe
+
+
+def test_cfg1_gpt2_small_full(dp, Pipe):
+    run_workload(dp, Pipe, "cfg1", full_layers=(0, 1, 2, 3))
+
+
+def test_cfg3_long_sequence_full(dp, Pipe):
+    pipe = run_workload(dp, Pipe, "cfg3", full_layers=(0, 1, 2, 3))
+    assert pipe.paths == [dp.DP_PATH_PEREX] * 4
+
+
+def test_cfg2_gpt2_large_full(dp, Pipe):
+    run_workload(dp, Pipe, "cfg2")
+
+
+def test_cfg4_wide_block_shard(dp, Pipe):
+    run_workload(dp, Pipe, "cfg4")
+
+
+# ----------------------------------------------------------------------------
+# error paths: every refusal happens on the host, nothing is launched
+# ----------------------------------------------------------------------------
+
+def test_argument_errors(dp):
+    x = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    lib = dp.lib
+    p = x.data_ptr()
+    INV, WSP = dp.DP_ERR_INVALID_ARG, dp.DP_ERR_WORKSPACE
+    assert lib.dp_ghost_norm(None, p, 1, 1, 8, 8, 8, p, p, 64, None) == INV
+    assert lib.dp_ghost_norm(p, p, 1, 1, 8, 12, 8, p, p, 64, None) == INV      # bf16 row not 16 B
+    assert lib.dp_ghost_norm(p, p, 1, 0, 8, 8, 8, p, p, 64, None) == INV
+    assert lib.dp_ghost_norm(p, p, 7, 1, 8, 8, 8, p, p, 64, None) == INV       # bad dtype
+    assert lib.dp_ghost_norm(p + 2, p, 1, 1, 8, 8, 8, p, p, 64, None) == INV   # misaligned
+    assert lib.dp_ghost_norm(p, p, 1, 1, 8, 8, 8, p, None, 0, None) == WSP
+    assert lib.dp_perex_norm(p, p, 1, 1, 8, 8, 8, p, p, 2, None) == WSP
+    assert lib.dp_clip_factors(p, 1, 1, 0, 0.0, 0.01, p, None, None) == INV
+    assert lib.dp_clip_factors(p, 1, 1, 0, float("nan"), 0.01, p, None, None) == INV
+    assert lib.dp_clip_factors(p, 1, 1, 2, 1.0, 0.01, p, None, None) == INV
+    assert lib.dp_clip_factors(p, 1, 1, 1, 1.0, -1.0, p, None, None) == INV
+    assert lib.dp_clipped_grad(p, p, 1, 1, 8, 8, 8, None, p, 0, None) == INV
+    assert lib.dp_clipped_grad(p, p, 1, 1, 8, 8, 8, p, p, 2, None) == INV
+    assert lib.dp_add_noise(p, 0, 16, -1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_add_noise(p, 0, 16, 1.0, float("inf"), 0, 0, None) == INV
+    assert lib.dp_add_noise(p + 1, 0, 16, 1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_add_noise(None, 0, 16, 1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_add_noise(p, 2 ** 64 - 4, 16, 1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_add_noise(p, 0, 0, 1.0, 1.0, 0, 0, None) == dp.DP_OK
+    torch.cuda.synchronize()
+    assert not host(x).any()
