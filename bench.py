@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the Book-Keeping clipped-gradient path on one MI355X.
+
+One step = the whole hot path over one synthetic micro-batch: per-layer per-sample norms
+(ghost or instantiated by the path rule) -> clip factors -> clip-weighted gradients of every
+layer -> Gaussian noise on the rank's shard.  Inputs are resident in HBM before timing.
+
+Prints ONE JSON line: samples/s, ms per step, per-stage times, the roofline of the dominant
+kernel (the clip-weighted gradient GEMM, measured with events around its launches inside the
+timed loop) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+PEAK_BF16_FLOPS = 2.5e15       # MI355X dense bf16 MFMA
+PEAK_HBM_BYTES = 8.0e12
+
+
+def workload_flops(w):
+    BT = w.B * w.T
+    grad = sum(2.0 * BT * d * p for d, p in w.layers)
+    norm = 0.0
+    for d, p in w.layers:
+        ghost = 2 * w.T * w.T <= d * p
+        norm += 2.0 * w.B * w.T * w.T * (d + p) if ghost else 2.0 * BT * d * p
+    return norm, grad
+
+
+def cpu_baseline(w, budget_layers):
+    """The oracle as it stands on the host cores, on the first `budget_layers` layers of the
+    workload (whole path on them: norms, clip factors, gradient, noise on their elements)."""
+    from oracle import bk_oracle as o
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    sub = si.Workload(**{**w.__dict__, "layers": w.layers[:budget_layers], "shard_count": 1, "shard_rank": 0})
+    layers = [tuple(si.to_f64(x) for x in si.gen_layer(sub, l)) for l in range(sub.L)]
+    t0 = time.perf_counter()
+    o.private_gradient(layers, sub.clip_mode, sub.R, sub.sigma, sub.stability, sub.noise_seed,
+                       sub.noise_step, 0, sub.psi)
+    dt = time.perf_counter() - t0
+    n_sub, g_sub = workload_flops(sub)
+    n_all, g_all = workload_flops(w)
+    scale = (n_all + g_all) / (n_sub + g_sub)
+    return {
+        "value": w.B / (dt * scale), "unit": "samples/s", "cores": cores, "kind": "oracle",
+        "sample": f"whole path on the first {budget_layers} of {w.L} layers ({dt:.2f} s of float64 numpy), "
+                  f"scaled by the flop ratio {scale:.2f}",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg1", choices=sorted(si.WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2311_11822_amd import binding as dp
+    from paper_2311_11822_amd.pipeline import BkPipeline
+
+    w = si.WORKLOADS[args.workload]
+    baseline = None
+    if not args.no_cpu_baseline:
+        budget = {"cfg0": 1, "cfg1": 48, "cfg2": 16, "cfg3": 4, "cfg4": 1}[w.name]
+        baseline = cpu_baseline(w, budget)
+
+    layers = []
+    for l in range(w.L):
+        a, g = si.gen_layer(w, l)
+        view = (lambda x: x.view(np.int16)) if w.dtype == si.BF16 else (lambda x: x)
+        layers.append((torch.from_numpy(view(a)).cuda(), torch.from_numpy(view(g)).cuda()))
+    pipe = BkPipeline(layers)
+    off, cnt = w.noise_range()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        pipe.norms()
+        if ev:
+            ev[1].record()
+        pipe.clip(w.clip_mode, w.R, w.stability)
+        if ev:
+            ev[2].record()
+        pipe.grad()
+        if ev:
+            ev[3].record()
+        pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+        if ev:
+            ev[4].record()
+
+    for _ in range(args.warmup):
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    stage = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(4)] for e in events])   # ms
+    ms_norm, ms_clip, ms_grad, ms_noise = stage.mean(axis=0)
+    ms_step = elapsed * 1e3 / args.steps
+    norm_flops, grad_flops = workload_flops(w)
+    grad_launches = -(-w.L // 48) if w.dtype == si.BF16 else w.L
+    grad_tflops = grad_flops / (ms_grad * 1e-3) / 1e12
+    out = {
+        "metric": "clipped-gradient samples/sec",
+        "value": w.B / (ms_step * 1e-3),
+        "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == si.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} T={w.T} L={w.L} layers, psi={w.psi}",
+                   "clip": "automatic" if w.clip_mode == si.CLIP_AUTOMATIC else "standard",
+                   "R": w.R, "sigma": w.sigma, "noise_elements": cnt},
+        "tflops_nominal": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,
+        "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
+        "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
+        "noise_gbps": 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
+        "roofline": {"kernel": "clipped_grad_kernel", "bound": "mfma",
+                     "achieved": grad_tflops, "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
+                     "frac": grad_tflops * 1e12 / PEAK_BF16_FLOPS,
+                     "launches_per_step": grad_launches,
+                     "avg_launch_ms": ms_grad / grad_launches,
+                     "traffic": None},
+        "cpu_baseline": baseline,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
