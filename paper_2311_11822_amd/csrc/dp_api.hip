@@ -209,34 +209,47 @@ dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int 
     }
     return DP_OK;
   }
-  int l = 0;
-  while (l < L) {
-    GroupArgs ga;
-    ga.B = B;
-    ga.accumulate = accumulate;
-    ga.n_layers = 0;
-    int64_t blocks = 0;
-    while (l < L && ga.n_layers < kMaxGroup) {
-      const int64_t tiles = clipped_grad_tiles(layers[l].d_in, layers[l].d_out);
-      if (ga.n_layers > 0 && blocks + tiles > INT32_MAX / 2) break;
-      GroupLayer& gl = ga.layer[ga.n_layers++];
-      gl.a = layers[l].a;
-      gl.g = layers[l].g;
-      gl.out = grads[l];
-      gl.T = layers[l].T;
-      gl.d_in = layers[l].d_in;
-      gl.d_out = layers[l].d_out;
-      gl.path = 0;
-      gl.tile_begin = (int)blocks;
-      gl.sq_index = l;
-      gl.part_begin = 0;
-      gl.tiles_per_sample = (int)tiles;
-      blocks += tiles;
-      ++l;
+  // Layers wide enough to fill 256x256 tiles take the large-tile kernel; the rest (and slabs
+  // beyond its 32-bit addressing) take the 8-wave kernel with per-element edge handling.
+  std::vector<int> big, small;
+  for (int l = 0; l < L; ++l) {
+    const dp_layer& ly = layers[l];
+    const bool use_big = ly.d_in >= 128 && ly.d_out >= 128 && clipped_grad_big_supports(ly.T, ly.d_in, ly.d_out);
+    (use_big ? big : small).push_back(l);
+  }
+  for (int pass = 0; pass < 2; ++pass) {
+    const std::vector<int>& which = pass == 0 ? big : small;
+    size_t pos = 0;
+    while (pos < which.size()) {
+      GroupArgs ga;
+      ga.B = B;
+      ga.accumulate = accumulate;
+      ga.n_layers = 0;
+      int64_t blocks = 0;
+      while (pos < which.size() && ga.n_layers < kMaxGroup) {
+        const int l = which[pos];
+        const int64_t tiles = pass == 0 ? clipped_grad_big_tiles(layers[l].d_in, layers[l].d_out)
+                                        : clipped_grad_tiles(layers[l].d_in, layers[l].d_out);
+        if (ga.n_layers > 0 && blocks + tiles > INT32_MAX / 2) break;
+        GroupLayer& gl = ga.layer[ga.n_layers++];
+        gl.a = layers[l].a;
+        gl.g = layers[l].g;
+        gl.out = grads[l];
+        gl.T = layers[l].T;
+        gl.d_in = layers[l].d_in;
+        gl.d_out = layers[l].d_out;
+        gl.path = 0;
+        gl.tile_begin = (int)blocks;
+        gl.sq_index = l;
+        gl.part_begin = 0;
+        gl.tiles_per_sample = (int)tiles;
+        blocks += tiles;
+        ++pos;
+      }
+      ga.total_blocks = (int)blocks;
+      dp_status st = pass == 0 ? launch_clipped_grad_big_group(ga, C, s) : launch_clipped_grad_group(ga, C, s);
+      if (st != DP_OK) return st;
     }
-    ga.total_blocks = (int)blocks;
-    dp_status st = launch_clipped_grad_group(ga, C, s);
-    if (st != DP_OK) return st;
   }
   return DP_OK;
 }
