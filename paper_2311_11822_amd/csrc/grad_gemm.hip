@@ -12,10 +12,10 @@
 //    spreads four consecutive k rows over the four 64-byte bank groups the transposing read
 //    touches at once.  Out-of-range chunks (tile edge, ragged T, past the last k-block) are
 //    fetched with an offset past the buffer descriptor's size and arrive as zeros.
-//  * four LDS stages of 32 k rows.  In iteration i a wave waits for its own loads of k-block
-//    i+1, meets the others at one barrier (which certifies block i+1 in LDS and block i-1 no
-//    longer read), issues the loads of block i+3 into the stage block i-1 used, and computes
-//    block i.  Operand fragments of the next k-step are fetched from LDS during the MFMAs of
+//  * five LDS stages of 32 k rows (all 160 KiB of the CU).  In iteration i a wave waits for its
+//    own loads of k-block i+1, meets the others at one barrier (which certifies block i+1 in
+//    LDS and block i-1 no longer read), issues the loads of block i+4 into the stage block i-1
+//    used, and computes block i.  A load has three iterations (about 3000 clocks) to land.  Operand fragments of the next k-step are fetched from LDS during the MFMAs of
 //    the current one, across the barrier too, so the matrix pipe never waits for LDS latency.
 //    The loads are issued from inline assembly because the compiler otherwise waits for every
 //    outstanding LDS-DMA load before any LDS read; MFMAs, LDS reads and loads are interleaved
@@ -32,12 +32,15 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
-constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = 4;
+#ifndef DP_GRAD_NSTAGE
+#define DP_GRAD_NSTAGE 5
+#endif
+constexpr int BM = 256, BN = 256, BK = 32, NSTAGE = DP_GRAD_NSTAGE;
 constexpr int NT = 256;
 constexpr int ROW_BYTES = 512;                         // 256 bf16
 constexpr int TILE_BYTES = BK * ROW_BYTES;             // one operand, one stage (16 KiB)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;            // 32 KiB
-constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;        // 128 KiB
+constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;        // 160 KiB with 5 stages: all of the CU's LDS
 constexpr int LOADS = BK / 8;                          // per operand per thread per k-block
 constexpr unsigned OOB = 0x80000000u;
 
@@ -162,7 +165,7 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
       while (p_i < B && C[p_i] == 0.f) ++p_i;
       prefetch_sample();
     }
-    p_stage = (p_stage + 1) & (NSTAGE - 1);
+    p_stage = p_stage + 1 == NSTAGE ? 0 : p_stage + 1;
   };
 
   // ---- LDS -> MFMA operand addressing ---------------------------------------------------
@@ -210,23 +213,23 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
   float held = 0.f;
   if (c_i < B) {
     held = C[c_i];
-    // prologue: blocks 0, 1, 2 in flight; block 0 complete in LDS
+    // prologue: blocks 0 .. NSTAGE-2 in flight; block 0 complete in LDS
     for (int q = 0; q < NSTAGE - 1; ++q) {
 #pragma unroll
       for (int j = 0; j < LOADS; ++j) prefetch_issue(j);
       prefetch_advance();
     }
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LOADS) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * 2 * LOADS) : "memory");
     __syncthreads();
 
     int c_stage = 0;
-    // One k-block: wait for block +1, barrier, issue block +3, 32 MFMAs.  `last` = last block
+    // One k-block: wait for block +1, barrier, issue block +(NSTAGE-1), 32 MFMAs.  `last` = last block
     // of the sample: the fragments of the following block are not fetched here.
     auto block = [&](auto last_tag) {
       constexpr bool last = decltype(last_tag)::value;
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 3) * 2 * LOADS) : "memory");
       __builtin_amdgcn_s_barrier();
-      const int n_stage = (c_stage + 1) & (NSTAGE - 1);
+      const int n_stage = c_stage + 1 == NSTAGE ? 0 : c_stage + 1;
       DP_PIN();
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
