@@ -81,36 +81,59 @@ struct Frag {
 
 #define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
+// Tile t of the launch -> layer and tile origin.  Inside a layer, tiles are numbered so that
+// 32 consecutive numbers form a patch of 4 tile rows x 8 tile columns and 8 consecutive
+// patches form a 16 x 16 super-patch (clamped at the layer's edges): 32 compute units of one
+// XCD then pull 12 operand panels per 32 tiles through that XCD's L2, and the 8 XCDs 32 panels
+// per 256 tiles through the memory-side cache.
+__device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& layer, int& m0, int& n0) {
+  int l = 0;
+  while (l + 1 < ga.n_layers && t >= ga.layer[l + 1].tile_begin) ++l;
+  layer = l;
+  const GroupLayer& ly = ga.layer[l];
+  int rem = t - ly.tile_begin;
+  const int tiles_m = (ly.d_in + BM - 1) / BM, tiles_n = (ly.d_out + BN - 1) / BN;
+  const int sr = min(rem / (16 * tiles_n), (tiles_m - 1) / 16);      // super-patch row
+  rem -= sr * 16 * tiles_n;
+  const int hm = min(16, tiles_m - 16 * sr);
+  const int sc = min(rem / (hm * 16), (tiles_n - 1) / 16);           // super-patch column
+  rem -= sc * hm * 16;
+  const int wn = min(16, tiles_n - 16 * sc);
+  const int pr = min(rem / (4 * wn), (hm - 1) / 4);                  // patch row inside it
+  rem -= pr * 4 * wn;
+  const int ph = min(4, hm - 4 * pr);
+  const int pc = min(rem / (ph * 8), (wn - 1) / 8);                  // patch column
+  rem -= pc * ph * 8;
+  m0 = (16 * sr + 4 * pr + rem % ph) * BM;
+  n0 = (16 * sc + 8 * pc + rem / ph) * BN;
+}
+
 __global__ void __launch_bounds__(NT)
-clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
+clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) {
+  // The weights do not change during the kernel: read them through the constant address space
+  // so that they come by scalar loads (a vector load here would make the compiler wait for
+  // every outstanding prefetch load at each sample boundary).
+  const __attribute__((address_space(4))) float* C =
+      (const __attribute__((address_space(4))) float*)(uintptr_t)C_global;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   const unsigned lds0 = (unsigned)(uintptr_t)lds_raw;
 
-  // XCD-aware order: consecutive block ids go to different XCDs (round-robin dispatch), so
-  // give each XCD one contiguous range of logical tiles; its L2 then sees neighbouring tiles.
+  // XCD-aware order.  Workgroup b runs on XCD b % 8 (round-robin dispatch) and about 256
+  // consecutive ids are resident at a time.  Within each run of 256 ids, XCD x gets the x-th
+  // group of 32 consecutive tile numbers, i.e. one 4 x 8 patch of locate_tile's numbering, and
+  // the eight XCDs together one 16 x 16 super-patch.
   int logical;
   {
-    const int n = ga.total_blocks, q = n >> 3, r = n & 7;
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    logical = xcd < r ? xcd * (q + 1) + idx : r * (q + 1) + (xcd - r) * q + idx;
+    constexpr int ROUND = 256;
+    const int base = (blockIdx.x / ROUND) * ROUND, q = blockIdx.x - base;
+    const int n = min(ROUND, ga.total_blocks - base);
+    const int per = n >> 3, rest = n & 7, xcd = q & 7, idx = q >> 3;
+    logical = base + (xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx);
   }
-  int l = 0;
-  while (l + 1 < ga.n_layers && logical >= ga.layer[l + 1].tile_begin) ++l;
+  int l, m0, n0;
+  locate_tile(ga, logical, l, m0, n0);
   const GroupLayer& ly = ga.layer[l];
-  const int local = logical - ly.tile_begin;
   const int T = ly.T, d = ly.d_in, p = ly.d_out;
-  const int tiles_m = (d + BM - 1) / BM, tiles_n = (p + BN - 1) / BN;
-  // grouped order: 4 tile rows at a time, columns inside the group vary slowest
-  int tm, tn;
-  {
-    constexpr int GM = 4;
-    const int per_group = GM * tiles_n;
-    const int grp = local / per_group, in = local % per_group;
-    const int rows = min(GM, tiles_m - grp * GM);
-    tm = grp * GM + in % rows;
-    tn = in / rows;
-  }
-  const int m0 = tm * BM, n0 = tn * BN;
   const int B = ga.B;
   const int nkb = (T + BK - 1) / BK;
 
@@ -151,10 +174,11 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
   };
   prefetch_sample();
   // One of the LOADS load pairs of the current prefetch block.
-  auto prefetch_issue = [&](int j) {
-    const unsigned dst = lds_ld + p_stage * STAGE_BYTES + j * 8 * ROW_BYTES;
-    load_to_lds(ra, va, sa + j * a_step, dst);
-    load_to_lds(rb, vb, sb + j * b_step, dst + TILE_BYTES);
+  auto prefetch_issue_a = [&](int j) {
+    load_to_lds(ra, va, sa + j * a_step, lds_ld + p_stage * STAGE_BYTES + j * 8 * ROW_BYTES);
+  };
+  auto prefetch_issue_b = [&](int j) {
+    load_to_lds(rb, vb, sb + j * b_step, lds_ld + p_stage * STAGE_BYTES + j * 8 * ROW_BYTES + TILE_BYTES);
   };
   auto prefetch_advance = [&]() {
     sa += BK * d * 2u;
@@ -193,16 +217,17 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   Frag fa[2][4], fb[2][4];
-  // Fragment reads of k-step `ks` of the block in `stage`: item q in 0..7 reads fa[q] (q < 4)
-  // or fb[q - 4].
+  // Fragment reads of k-step `ks` of the block in `stage`: item q in 0..7 reads fb[q] (q < 4)
+  // or fa[q - 4].  The first MFMA row of the next k-step needs every fb but only fa[0], so the
+  // B fragments go first and the last-issued read (fa[3]) is needed last.
   auto read_frag = [&](int buf, int q, int stage, int ks) {
     const unsigned o = stage * STAGE_BYTES + ks * 16 * ROW_BYTES;
     if (q < 4) {
-      fa[buf][q].h[0] = lds_read_tr(a_rd[q] + o);
-      fa[buf][q].h[1] = lds_read_tr(a_rd[q] + o + 4 * ROW_BYTES);
+      fb[buf][q].h[0] = lds_read_tr(b_rd[q] + o);
+      fb[buf][q].h[1] = lds_read_tr(b_rd[q] + o + 4 * ROW_BYTES);
     } else {
-      fb[buf][q - 4].h[0] = lds_read_tr(b_rd[q - 4] + o);
-      fb[buf][q - 4].h[1] = lds_read_tr(b_rd[q - 4] + o + 4 * ROW_BYTES);
+      fa[buf][q - 4].h[0] = lds_read_tr(a_rd[q - 4] + o);
+      fa[buf][q - 4].h[1] = lds_read_tr(a_rd[q - 4] + o + 4 * ROW_BYTES);
     }
   };
 
@@ -216,7 +241,10 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
     // prologue: blocks 0 .. NSTAGE-2 in flight; block 0 complete in LDS
     for (int q = 0; q < NSTAGE - 1; ++q) {
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j) prefetch_issue(j);
+      for (int j = 0; j < LOADS; ++j) {
+        prefetch_issue_a(j);
+        prefetch_issue_b(j);
+      }
       prefetch_advance();
     }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * 2 * LOADS) : "memory");
@@ -248,7 +276,10 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
           DP_PIN();
           acc[g][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][g].v, fb[cb][2].v, acc[g][2], 0, 0, 0);
           DP_PIN();
-          if (g & 1) prefetch_issue(ks * 2 + (g >> 1));
+          if (g & 1)
+            prefetch_issue_b(ks * 2 + (g >> 1));
+          else
+            prefetch_issue_a(ks * 2 + (g >> 1));
           DP_PIN();
           acc[g][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][g].v, fb[cb][3].v, acc[g][3], 0, 0, 0);
           DP_PIN();
@@ -307,23 +338,37 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // zero-fill loads past the end
   }
 
+  // epilogue: grad (+)= held * acc.  With no active sample the accumulator is zero.
   float* out = ly.out;
+  auto store_tile = [&](auto acc_tag) {
+    constexpr bool accumulate = decltype(acc_tag)::value;
 #pragma unroll
-  for (int x = 0; x < 4; ++x)
+    for (int x = 0; x < 4; ++x)
 #pragma unroll
-    for (int y = 0; y < 4; ++y) {
-      const int col = n0 + wn + y * 32 + (lane & 31);
+      for (int y = 0; y < 4; ++y) {
+        const int col = n0 + wn + y * 32 + (lane & 31);
+        float* base = out + (size_t)(m0 + wm + x * 32 + 4 * (lane >> 5)) * p + col;
+        float old[16];
+        if (accumulate) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm + x * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < d && col < p) {
-          float* dst = out + (size_t)row * p + col;
-          const float v = acc[x][y][r] * held;
-          *dst = ga.accumulate ? *dst + v : v;
+          for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm + x * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            old[r] = (row < d && col < p) ? base[(size_t)(8 * (r >> 2) + (r & 3)) * p] : 0.f;
+          }
         }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm + x * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const float v = acc[x][y][r] * held;
+          if (row < d && col < p) base[(size_t)(8 * (r >> 2) + (r & 3)) * p] = accumulate ? old[r] + v : v;
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
-    }
+  };
+  if (ga.accumulate)
+    store_tile(std::true_type{});
+  else
+    store_tile(std::false_type{});
 }
 
 }  // namespace
