@@ -25,13 +25,22 @@ dp_status check_layer_ptrs(const void* a, const void* g) {
   return DP_OK;
 }
 
+// Ghost layers with whole 64-wide k-blocks and more than a handful of tokens take the
+// large-tile kernel; the rest take the 128x128-tile kernel with per-chunk edge handling.
+bool ghost_uses_big(const dp_layer& ly) {
+  return ly.T >= 96 && ghost_big_supports(ly.T, ly.d_in, ly.d_out);
+}
+
 int tiles_per_sample(int path, const dp_layer& ly) {
-  return path == DP_PATH_GHOST ? ghost_tiles_per_sample(ly.T) : perex_tiles_per_sample(ly.d_in, ly.d_out);
+  if (path == DP_PATH_PEREX) return perex_tiles_per_sample(ly.d_in, ly.d_out);
+  return ghost_uses_big(ly) ? ghost_big_tiles_per_sample(ly.T) : ghost_tiles_per_sample(ly.T);
 }
 
 // Launches the norm kernels of one path for the listed layers, in chunks of kMaxGroup.
 // part_begin[l] is the layer's first slot in the partial-sum workspace.
-dp_status run_norm_path(int path, const dp_layer* layers, const std::vector<int>& which,
+enum NormKernel { kGhostBig, kGhostSmall, kPerex };
+
+dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, const std::vector<int>& which,
                         const std::vector<int64_t>& part_begin, int B, float* partials,
                         float* sqnorm_out, hipStream_t s) {
   for (size_t begin = 0; begin < which.size(); begin += kMaxGroup) {
@@ -49,16 +58,17 @@ dp_status run_norm_path(int path, const dp_layer* layers, const std::vector<int>
       gl.T = layers[l].T;
       gl.d_in = layers[l].d_in;
       gl.d_out = layers[l].d_out;
-      gl.path = path;
+      gl.path = kernel == kPerex ? DP_PATH_PEREX : DP_PATH_GHOST;
       gl.tile_begin = (int)blocks;
       gl.sq_index = l;
       gl.part_begin = (int)part_begin[l];
-      gl.tiles_per_sample = tiles_per_sample(path, layers[l]);
+      gl.tiles_per_sample = tiles_per_sample(gl.path, layers[l]);
       blocks += (int64_t)gl.tiles_per_sample * B;
     }
     ga.total_blocks = (int)blocks;
-    dp_status st = path == DP_PATH_GHOST ? launch_ghost_group(ga, partials, s)
-                                         : launch_perex_group(ga, partials, s);
+    dp_status st = kernel == kGhostBig     ? launch_ghost_big_group(ga, partials, s)
+                   : kernel == kGhostSmall ? launch_ghost_group(ga, partials, s)
+                                           : launch_perex_group(ga, partials, s);
     if (st != DP_OK) return st;
     st = launch_norm_reduce_group(ga, partials, sqnorm_out, s);
     if (st != DP_OK) return st;
@@ -105,12 +115,19 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
   }
   if (!ws || ws_bytes < (size_t)slots * sizeof(float)) return DP_ERR_WORKSPACE;
   if (!aligned16(ws)) return DP_ERR_INVALID_ARG;
-  std::vector<int> ghost, perex;
-  for (int l = 0; l < L; ++l) (layers[l].path == DP_PATH_GHOST ? ghost : perex).push_back(l);
+  std::vector<int> ghost_big, ghost_small, perex;
+  for (int l = 0; l < L; ++l) {
+    if (layers[l].path == DP_PATH_PEREX)
+      perex.push_back(l);
+    else
+      (ghost_uses_big(layers[l]) ? ghost_big : ghost_small).push_back(l);
+  }
   float* partials = static_cast<float*>(ws);
-  dp_status st = run_norm_path(DP_PATH_GHOST, layers, ghost, begin, B, partials, sqnorm_out, s);
+  dp_status st = run_norm_path(kGhostBig, layers, ghost_big, begin, B, partials, sqnorm_out, s);
   if (st != DP_OK) return st;
-  return run_norm_path(DP_PATH_PEREX, layers, perex, begin, B, partials, sqnorm_out, s);
+  st = run_norm_path(kGhostSmall, layers, ghost_small, begin, B, partials, sqnorm_out, s);
+  if (st != DP_OK) return st;
+  return run_norm_path(kPerex, layers, perex, begin, B, partials, sqnorm_out, s);
 }
 
 dp_status single_norm(dp_path path, const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,

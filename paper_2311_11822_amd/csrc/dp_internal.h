@@ -64,6 +64,10 @@ dp_status launch_perex_group(const GroupArgs& ga, float* partials, hipStream_t s
 dp_status launch_norm_reduce_group(const GroupArgs& ga, const float* partials, float* sqnorm_out,
                                    hipStream_t s);
 dp_status launch_clipped_grad_group(const GroupArgs& ga, const float* C, hipStream_t s);
+// 256x128-tile ghost-norm kernel with direct global->LDS loads (ghost_big.hip).
+int ghost_big_tiles_per_sample(int T);
+bool ghost_big_supports(int T, int d, int p);
+dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream_t s);
 // 256x256-tile kernel with direct global->LDS loads (grad_gemm.hip).
 int clipped_grad_big_tiles(int d, int p);
 bool clipped_grad_big_supports(int T, int d, int p);

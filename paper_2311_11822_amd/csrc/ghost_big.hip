@@ -1,0 +1,275 @@
+// Ghost norm on the matrix cores, large-tile kernel (appendix A.1 of the paper, right side of
+// eq. "mixed ghost norm"):  sqnorm[i] = sum_{t,t'} (a_t . a_t') (g_t . g_t')  for sample i.
+//
+// One workgroup owns a 256 x 128 tile (token rows [256 I, +256), token columns [128 J, +128),
+// J >= 2 I) of both T x T Gram matrices of one sample: it accumulates the tile of a a^T over
+// d_in, then the tile of g g^T over d_out, in two accumulator sets (4 waves x 128 x 64 x 2 sets
+// = all 256 accumulator registers per lane), multiplies them element by element and reduces to
+// one partial sum.  Both Gram matrices are symmetric, so 128 x 128 sub-blocks above the
+// diagonal count twice, diagonal ones once and the one sub-block per tile row that lies below
+// the diagonal is skipped.  No T x T matrix is written to memory.
+//
+// Data path (same machinery as the gradient kernel in grad_gemm.hip): operand rows go from
+// global memory to LDS without passing through registers (buffer_load ... lds), three stages
+// of 64 k each, issued two k-blocks ahead across the a -> g switch; rows are k-contiguous
+// in memory, in LDS and in the MFMA operand, so fragments come back with plain 128-bit LDS
+// reads.  A wave's load lands as eight consecutive 128-byte rows, so rows cannot be padded;
+// the 16-byte chunks of row r are XOR-swizzled by (r >> 1) & 7, which makes 16 consecutive
+// rows of one k-chunk hit 16 different bank groups.  Token rows past T are fetched past the
+// end of the sample's buffer descriptor and arrive as zeros.  When the column block lies
+// inside the row block (J = 2I or 2I+1, always the case for T <= 256) it is not loaded again.
+#include <type_traits>
+
+#include "dp_internal.h"
+
+namespace dpbk {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+constexpr int TI = 256, TJ = 128, BK = 64, NSTAGE = 3;
+constexpr int NT = 256;
+constexpr int ROW_BYTES = 128;                       // 64 bf16
+constexpr int I_BYTES = TI * ROW_BYTES;              // 32 KiB
+constexpr int J_BYTES = TJ * ROW_BYTES;              // 16 KiB
+constexpr int STAGE_BYTES = I_BYTES + J_BYTES;       // 48 KiB
+constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;      // 144 KiB
+constexpr int LOADS_I = 8, LOADS_J = 4;              // per wave per k-block (a wave-load = 8 rows)
+
+__device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  i32x4 r;
+  r[0] = (int)(uint32_t)p;
+  r[1] = (int)(uint32_t)(p >> 32) & 0xFFFF;          // stride 0: raw buffer
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
+
+// 16 bytes per lane from buffer `rsrc` at byte voff + soff to LDS at lds_base + 16*lane.
+// The range check sees voff: a lane whose voff is past the descriptor's size fetches zeros.
+__device__ __forceinline__ void load_to_lds(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "buffer_load_dwordx4 %1, %2, %3 offen lds"
+      :
+      : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
+      : "memory", "m0");
+}
+
+__device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
+  return *(__attribute__((address_space(3))) bf16x8*)(uintptr_t)addr;
+}
+
+#define DP_PIN() __builtin_amdgcn_sched_barrier(0)
+
+__global__ void __launch_bounds__(NT)
+ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
+  const unsigned lds0 = (unsigned)(uintptr_t)lds_raw;
+
+  int l = 0;
+  while (l + 1 < ga.n_layers && (int)blockIdx.x >= ga.layer[l + 1].tile_begin) ++l;
+  const GroupLayer& ly = ga.layer[l];
+  const int local = blockIdx.x - ly.tile_begin;
+  const int sample = local / ly.tiles_per_sample;
+  int q = local % ly.tiles_per_sample;
+  const int T = ly.T;
+  // q enumerates tiles (I, J), J >= 2I, row by row; a tile row I has nj - 2I tiles.
+  const int nj = (T + TJ - 1) / TJ;
+  int I = 0;
+  while (q >= nj - 2 * I) {
+    q -= nj - 2 * I;
+    ++I;
+  }
+  const int J = 2 * I + q;
+  const int r0 = I * TI, c0 = J * TJ;
+  const bool inside = q < 2;                      // column block is one half of the row block
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 64;
+  // weight of this wave's 128 x 128 sub-block (rows r0 + wm): above / on / below the diagonal
+  const int sub_row = 2 * I + (wave >> 1);
+  const float weight = J > sub_row ? 2.f : (J == sub_row ? 1.f : 0.f);
+
+  // ---- prefetch stream ---------------------------------------------------------------
+  // Wave-load j of the row block covers rows (wave*8 + j)*8 + (lane >> 3); the lane's LDS chunk
+  // (lane & 7) holds logical chunk (lane & 7) ^ ((row >> 1) & 7).  Same for the column block
+  // with wave*4 + j.
+  const int nka = ly.d_in / BK, nkg = ly.d_out / BK, nblocks = nka + nkg;
+  unsigned vi[LOADS_I], vj[LOADS_J];
+  i32x4 rs;
+  auto set_operand = [&](const void* base, int width) {
+    const unsigned slab = (unsigned)T * width * 2u;
+    rs = make_rsrc(static_cast<const unsigned char*>(base) + (size_t)sample * slab, slab);
+#pragma unroll
+    for (int j = 0; j < LOADS_I; ++j) {
+      const int row = (wave * LOADS_I + j) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      vi[j] = (unsigned)(r0 + row) * width * 2u + chunk * 16u;     // rows >= T: past the slab -> zeros
+    }
+#pragma unroll
+    for (int j = 0; j < LOADS_J; ++j) {
+      const int row = (wave * LOADS_J + j) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      vj[j] = (unsigned)(c0 + row) * width * 2u + chunk * 16u;
+    }
+  };
+  int p_blk = 0, p_stage = 0;
+  unsigned p_soff = 0;
+  set_operand(ly.a, ly.d_in);
+  // item in 0 .. LOADS_I + LOADS_J - 1: one wave-load of the row block or of the column block
+  auto issue = [&](int item, bool with_j) {
+    const unsigned st = lds0 + p_stage * STAGE_BYTES;
+    if (item < LOADS_I)
+      load_to_lds(rs, vi[item], p_soff, st + (wave * LOADS_I + item) * 1024);
+    else if (with_j)
+      load_to_lds(rs, vj[item - LOADS_I], p_soff, st + I_BYTES + (wave * LOADS_J + item - LOADS_I) * 1024);
+  };
+  auto advance = [&]() {
+    ++p_blk;
+    p_soff += BK * 2;
+    p_stage = p_stage + 1 == NSTAGE ? 0 : p_stage + 1;
+    if (p_blk == nka) {
+      set_operand(ly.g, ly.d_out);
+      p_soff = 0;
+    } else if (p_blk == nblocks) {
+      // past the end of the stream: keep issuing (the waits count loads) but fetch nothing
+#pragma unroll
+      for (int j = 0; j < LOADS_I; ++j) vi[j] = 0x80000000u;
+#pragma unroll
+      for (int j = 0; j < LOADS_J; ++j) vj[j] = 0x80000000u;
+      p_soff = 0;
+    }
+  };
+
+  // ---- LDS -> MFMA operand addressing ---------------------------------------------------
+  // lane: row (lane & 31) of a 32-row MFMA tile, k-chunk 2*ks + (lane >> 5); swizzle
+  // (row >> 1) & 7 = (lane >> 1) & 7 because tile origins are multiples of 16 rows.
+  unsigned rd[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    rd[ks] = lds0 + (lane & 31) * ROW_BYTES + (((2 * ks + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+  const unsigned a_org = wm * ROW_BYTES;
+  const unsigned b_org = (inside ? (J - 2 * I) * TJ * ROW_BYTES : I_BYTES) + wn * ROW_BYTES;
+
+  f32x16 sa[4][2], sg[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        sa[i][j][r] = 0.f;
+        sg[i][j][r] = 0.f;
+      }
+
+  bf16x8 fa[2][4], fb[2][2];
+  // item 0,1: column-block fragments; 2..5: row-block fragments (needed in that order)
+  auto read_frag = [&](int buf, int item, int stage, int ks) {
+    const unsigned o = rd[ks] + stage * STAGE_BYTES;
+    if (item < 2)
+      fb[buf][item] = lds_read16(o + b_org + item * 32 * ROW_BYTES);
+    else
+      fa[buf][item - 2] = lds_read16(o + a_org + (item - 2) * 32 * ROW_BYTES);
+  };
+
+  // Loads per k-block differ (12, or 8 when the column block is inside the row block); the
+  // vmcnt immediates must be constants, hence two instantiations of the loop.
+  //
+  // Iteration kb: a wave waits for its own loads of block kb, meets the others at one barrier
+  // (block kb is in LDS, block kb-1 is no longer read), fetches the first fragments, then runs
+  // 32 MFMAs with the loads of block kb+2 (into the stage of block kb-1) and the fragment reads
+  // of the next k-step in their shadow.  A load has two iterations to land.
+  auto run = [&](auto inside_tag) {
+    constexpr bool ins = decltype(inside_tag)::value;
+    constexpr int PER = ins ? LOADS_I : LOADS_I + LOADS_J;
+    for (int s = 0; s < NSTAGE - 1; ++s) {
+#pragma unroll
+      for (int it = 0; it < LOADS_I + LOADS_J; ++it) issue(it, !ins);
+      advance();
+    }
+    int c_stage = 0;
+    auto block = [&](f32x16 (&acc)[4][2]) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * PER) : "memory");
+      __builtin_amdgcn_s_barrier();
+#pragma unroll
+      for (int it = 0; it < 6; ++it) read_frag(0, it, c_stage, 0);
+      DP_PIN();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int cb = ks & 1, nb = cb ^ 1;
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+          const int i = n >> 1, j = n & 1;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
+          DP_PIN();
+          if (ks < 3 && n < 6) read_frag(nb, n, c_stage, ks + 1);
+          // 12 loads over 4 k-steps: after MFMA 3, 5 and 6 of each
+          if (n == 3) issue(ks * 3, !ins);
+          if (n == 5) issue(ks * 3 + 1, !ins);
+          if (n == 6) issue(ks * 3 + 2, !ins);
+          DP_PIN();
+        }
+      }
+      advance();
+      c_stage = c_stage + 1 == NSTAGE ? 0 : c_stage + 1;
+    };
+    for (int kb = 0; kb < nka; ++kb) block(sa);
+    for (int kb = 0; kb < nkg; ++kb) block(sg);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+  if (inside)
+    run(std::true_type{});
+  else
+    run(std::false_type{});
+
+  // Token rows/columns past T were fetched as zeros: their Gram entries are zero.
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s = fmaf(sa[i][j][r], sg[i][j][r], s);
+  s *= weight;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+  __syncthreads();                                  // every wave is done with the stages
+  float* red = reinterpret_cast<float*>(lds_raw);
+  if (lane == 0) red[wave] = s;
+  __syncthreads();
+  if (tid == 0) partials[ly.part_begin + local] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+}  // namespace
+
+int ghost_big_tiles_per_sample(int T) {
+  const int nj = (T + TJ - 1) / TJ, ni = (T + TI - 1) / TI;
+  int n = 0;
+  for (int I = 0; I < ni; ++I) n += nj - 2 * I;
+  return n;
+}
+
+// Needs whole 64-wide k-blocks and 32-bit byte offsets inside a sample's slab.
+bool ghost_big_supports(int T, int d, int p) {
+  return d % BK == 0 && p % BK == 0 && (int64_t)(T + TI) * d * 2 < (int64_t)1 << 31 &&
+         (int64_t)(T + TI) * p * 2 < (int64_t)1 << 31;
+}
+
+dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream_t s) {
+  static bool ready = false;
+  if (!ready) {
+    dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(ghost_big_kernel),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    if (st != DP_OK) return st;
+    ready = true;
+  }
+  hipLaunchKernelGGL(ghost_big_kernel, dim3(ga.total_blocks), dim3(NT), LDS_BYTES, s, ga, partials);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace dpbk
