@@ -126,6 +126,15 @@ def main():
     norm_flops, grad_flops = workload_flops(w)
     grad_launches = -(-w.L // 48) if w.dtype == si.BF16 else w.L
     grad_tflops = grad_flops / (ms_grad * 1e-3) / 1e12
+    # HBM-side bytes per launch of the dominant kernel, from the committed rocprofv3 counter runs
+    # (profiles/<workload>_all_kernels.md); null when this workload has not been profiled.
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            t = json.load(f)["per_launch"][w.name]["clipped_grad_big_kernel"]
+        traffic = t["fetch_bytes"] + t["write_bytes"]
+    except (OSError, KeyError, ValueError):
+        pass
     out = {
         "metric": "clipped-gradient samples/sec",
         "value": w.B / (ms_step * 1e-3),
@@ -142,12 +151,14 @@ def main():
         "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
         "noise_gbps": 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
-        "roofline": {"kernel": "clipped_grad_kernel", "bound": "mfma",
+        "roofline": {"kernel": "clipped_grad_big_kernel" if w.dtype == si.BF16 else "clipped_grad_f32_kernel",
+                     "bound": "mfma",
                      "achieved": grad_tflops, "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
                      "frac": grad_tflops * 1e12 / PEAK_BF16_FLOPS,
                      "launches_per_step": grad_launches,
                      "avg_launch_ms": ms_grad / grad_launches,
-                     "traffic": None},
+                     "algorithmic_flops_per_launch": grad_flops / grad_launches,
+                     "traffic": traffic},
         "cpu_baseline": baseline,
     }
     print(json.dumps(out))

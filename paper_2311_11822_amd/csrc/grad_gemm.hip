@@ -15,8 +15,8 @@
 //  * five LDS stages of 32 k rows (all 160 KiB of the CU).  In iteration i a wave waits for its
 //    own loads of k-block i+1, meets the others at one barrier (which certifies block i+1 in
 //    LDS and block i-1 no longer read), issues the loads of block i+4 into the stage block i-1
-//    used, and computes block i.  A load has three iterations (about 3000 clocks) to land.  Operand fragments of the next k-step are fetched from LDS during the MFMAs of
-//    the current one, across the barrier too, so the matrix pipe never waits for LDS latency.
+//    used, and computes block i.  A load has three iterations (about 3000 clocks) to land.
+//    Operand fragments of the next k-step are fetched from LDS during the MFMAs of the current one, across the barrier too, so the matrix pipe never waits for LDS latency.
 //    The loads are issued from inline assembly because the compiler otherwise waits for every
 //    outstanding LDS-DMA load before any LDS read; MFMAs, LDS reads and loads are interleaved
 //    by hand (one wave per SIMD: there is no second wave to hide issue gaps).
