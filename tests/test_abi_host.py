@@ -46,7 +46,7 @@ def test_path_rule_matches_oracle_reading(dp):
 
 
 def test_workspace_sizes(dp):
-    assert dp.dp_norm_workspace_bytes(0, 1, 16, 256, 768, 2304) >= 16 * 3 * 4
+    assert dp.dp_norm_workspace_bytes(0, 1, 16, 256, 768, 2304) >= 16 * 4      # at least one partial per sample
     assert dp.dp_norm_workspace_bytes(0, 1, 0, 256, 768, 2304) == 0
     assert dp.dp_norm_workspace_bytes(0, 1, 1, 256, 12, 8) == 0       # bf16 row not a multiple of 16 B
     assert dp.dp_norm_workspace_bytes(1, 0, 4, 8, 16, 16) > 0
