@@ -28,13 +28,21 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
-constexpr int TI = 256, TJ = 128, BK = 64, NSTAGE = 3;
+constexpr int TI = 256, TJ = 128, BK = 64;
 constexpr int NT = 256;
 constexpr int ROW_BYTES = 128;                       // 64 bf16
 constexpr int I_BYTES = TI * ROW_BYTES;              // 32 KiB
 constexpr int J_BYTES = TJ * ROW_BYTES;              // 16 KiB
-constexpr int STAGE_BYTES = I_BYTES + J_BYTES;       // 48 KiB
-constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;      // 144 KiB
+// Two LDS plans.  General: 3 stages of row block + column block (144 KiB).  Compact, for
+// launches whose layers all have T <= 256 (every column block lies inside its row block):
+// 5 stages of the row block alone (160 KiB), which buys a deeper prefetch and lets the
+// fragment reads run across the barrier.
+template <bool COMPACT>
+struct Plan {
+  static constexpr int STAGE_BYTES = COMPACT ? I_BYTES : I_BYTES + J_BYTES;
+  static constexpr int NSTAGE = COMPACT ? 5 : 3;
+  static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+};
 constexpr int LOADS_I = 8, LOADS_J = 4;              // per wave per k-block (a wave-load = 8 rows)
 
 __device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
@@ -65,8 +73,10 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
 
 #define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
+template <bool COMPACT>
 __global__ void __launch_bounds__(NT)
 ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
+  constexpr int STAGE_BYTES = Plan<COMPACT>::STAGE_BYTES, NSTAGE = Plan<COMPACT>::NSTAGE;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   const unsigned lds0 = (unsigned)(uintptr_t)lds_raw;
 
@@ -178,12 +188,12 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   };
 
   // Loads per k-block differ (12, or 8 when the column block is inside the row block); the
-  // vmcnt immediates must be constants, hence two instantiations of the loop.
+  // vmcnt immediates must be constants, hence separate instantiations of the loop.
   //
-  // Iteration kb: a wave waits for its own loads of block kb, meets the others at one barrier
-  // (block kb is in LDS, block kb-1 is no longer read), fetches the first fragments, then runs
-  // 32 MFMAs with the loads of block kb+2 (into the stage of block kb-1) and the fragment reads
-  // of the next k-step in their shadow.  A load has two iterations to land.
+  // General plan, iteration kb: a wave waits for its own loads of block kb, meets the others at
+  // one barrier (block kb is in LDS, block kb-1 is no longer read), fetches the first fragments,
+  // then runs 32 MFMAs with the loads of block kb+2 (into the stage of block kb-1) and the
+  // fragment reads of the next k-step in their shadow.  A load has two iterations to land.
   auto run = [&](auto inside_tag) {
     constexpr bool ins = decltype(inside_tag)::value;
     constexpr int PER = ins ? LOADS_I : LOADS_I + LOADS_J;
@@ -222,7 +232,54 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
     for (int kb = 0; kb < nkg; ++kb) block(sg);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
-  if (inside)
+  // Compact plan, iteration kb: wait for own loads of block kb+1, barrier (block kb+1 in LDS,
+  // block kb-1 no longer read), issue block kb+4, 32 MFMAs; the fragments of the next k-step,
+  // including the first one of block kb+1, are read during the MFMAs.  Three iterations per load.
+  auto run_compact = [&]() {
+    constexpr int PER = LOADS_I;
+    for (int s = 0; s < NSTAGE - 1; ++s) {
+#pragma unroll
+      for (int it = 0; it < LOADS_I; ++it) issue(it, false);
+      advance();
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * PER) : "memory");
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 6; ++it) read_frag(0, it, 0, 0);
+    int c_stage = 0;
+    auto block = [&](f32x16 (&acc)[4][2], auto last_tag) {
+      constexpr bool last = decltype(last_tag)::value;
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 3) * PER) : "memory");
+      __builtin_amdgcn_s_barrier();
+      const int n_stage = c_stage + 1 == NSTAGE ? 0 : c_stage + 1;
+      DP_PIN();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int cb = ks & 1, nb = cb ^ 1;
+        const bool fetch = ks < 3 || !last;
+        const int r_stage = ks < 3 ? c_stage : n_stage, r_ks = ks < 3 ? ks + 1 : 0;
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+          const int i = n >> 1, j = n & 1;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
+          DP_PIN();
+          if (fetch && n < 6) read_frag(nb, n, r_stage, r_ks);
+          if (n == 3) issue(ks * 2, false);            // 8 loads over 4 k-steps
+          if (n == 6) issue(ks * 2 + 1, false);
+          DP_PIN();
+        }
+      }
+      advance();
+      c_stage = n_stage;
+    };
+    for (int kb = 0; kb < nka; ++kb) block(sa, std::false_type{});
+    for (int kb = 0; kb + 1 < nkg; ++kb) block(sg, std::false_type{});
+    block(sg, std::true_type{});
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+  if (COMPACT)
+    run_compact();
+  else if (inside)
     run(std::true_type{});
   else
     run(std::false_type{});
@@ -260,16 +317,25 @@ bool ghost_big_supports(int T, int d, int p) {
          (int64_t)(T + TI) * p * 2 < (int64_t)1 << 31;
 }
 
-dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream_t s) {
+template <bool COMPACT>
+dp_status launch_plan(const GroupArgs& ga, float* partials, hipStream_t s) {
   static bool ready = false;
+  auto kernel = ghost_big_kernel<COMPACT>;
   if (!ready) {
-    dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(ghost_big_kernel),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                  Plan<COMPACT>::LDS_BYTES));
     if (st != DP_OK) return st;
     ready = true;
   }
-  hipLaunchKernelGGL(ghost_big_kernel, dim3(ga.total_blocks), dim3(NT), LDS_BYTES, s, ga, partials);
+  hipLaunchKernelGGL(kernel, dim3(ga.total_blocks), dim3(NT), Plan<COMPACT>::LDS_BYTES, s, ga, partials);
   return hip_status(hipGetLastError());
+}
+
+dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream_t s) {
+  bool compact = true;
+  for (int l = 0; l < ga.n_layers; ++l) compact = compact && ga.layer[l].T <= TI;
+  return compact ? launch_plan<true>(ga, partials, s) : launch_plan<false>(ga, partials, s);
 }
 
 }  // namespace dpbk

@@ -16,7 +16,8 @@
 //    own loads of k-block i+1, meets the others at one barrier (which certifies block i+1 in
 //    LDS and block i-1 no longer read), issues the loads of block i+4 into the stage block i-1
 //    used, and computes block i.  A load has three iterations (about 3000 clocks) to land.
-//    Operand fragments of the next k-step are fetched from LDS during the MFMAs of the current one, across the barrier too, so the matrix pipe never waits for LDS latency.
+//    Operand fragments of the next k-step are fetched from LDS during the MFMAs of the current
+//    one, across the barrier too, so the matrix pipe never waits for LDS latency.
 //    The loads are issued from inline assembly because the compiler otherwise waits for every
 //    outstanding LDS-DMA load before any LDS read; MFMAs, LDS reads and loads are interleaved
 //    by hand (one wave per SIMD: there is no second wave to hide issue gaps).
@@ -301,6 +302,7 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) 
         // through inline assembly.
         const float f = held / c;
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        if (f != 1.f)                       // equal weights (e.g. nothing clipped): nothing to do
 #pragma unroll
         for (int x = 0; x < 4; ++x)
 #pragma unroll
