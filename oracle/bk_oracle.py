@@ -88,6 +88,59 @@ def clip_factors(sqnorm: np.ndarray, mode: int, R: float, stability: float = 0.0
     return C, norm
 
 
+def clip_factors_grouped(sqnorm: np.ndarray, group_of_layer, R, mode: int, stability: float = 0.01):
+    """Group-wise clipping (eq. (1) with M groups; section 2.1, "Mathematical gradient
+    partition"): layer l belongs to group group_of_layer[l]; group m has its own threshold
+    R[m] and its own per-sample norm over the group's layers.  Layer-wise clipping is one
+    group per layer, all-layer clipping one group in all.  Returns (C [M,B], norm [M,B])."""
+    sqnorm = np.asarray(sqnorm, dtype=np.float64)
+    R = np.asarray(R, dtype=np.float64)
+    M, B = len(R), sqnorm.shape[1]
+    C = np.empty((M, B), dtype=np.float64)
+    norm = np.empty((M, B), dtype=np.float64)
+    for m in range(M):
+        rows = [l for l, gm in enumerate(group_of_layer) if gm == m]
+        if rows:
+            C[m], norm[m] = clip_factors(sqnorm[rows], mode, R[m], stability)
+        else:                                   # an empty group has zero gradient
+            C[m], norm[m] = clip_factors(np.zeros((1, B)), mode, R[m], stability)
+    return C, norm
+
+
+def group_noise_std(sigma: float, R) -> float:
+    """Standard deviation of the noise in eq. (1): sigma_DP * ||[R_1, ..., R_M]||_2."""
+    return float(sigma) * float(np.sqrt(np.sum(np.asarray(R, dtype=np.float64) ** 2)))
+
+
+# ----------------------------------------------------------------------------
+# Bias (appendix A.1, last paragraph): dL_i/db = 1^T dL/ds_i, norm by instantiation
+# ----------------------------------------------------------------------------
+
+def bias_per_sample_grad(g: np.ndarray) -> np.ndarray:
+    """Per-sample bias gradient: the sum of g[i] over its T token rows.  [B,T,p] -> [B,p]."""
+    B, T, p = g.shape
+    out = np.zeros((B, p), dtype=np.float64)
+    for i in range(B):
+        for t in range(T):
+            out[i] += g[i, t]
+    return out
+
+
+def bias_sqnorm(g: np.ndarray) -> np.ndarray:
+    """|| 1^T g_i ||^2 per sample."""
+    bg = bias_per_sample_grad(g)
+    return np.sum(bg * bg, axis=1)
+
+
+def clipped_bias_grad(g: np.ndarray, C: np.ndarray) -> np.ndarray:
+    """sum_i C_i 1^T g_i -> [p]."""
+    bg = bias_per_sample_grad(g)
+    out = np.zeros(g.shape[2], dtype=np.float64)
+    for i in range(g.shape[0]):
+        out += C[i] * bg[i]
+    return out
+
+
 # ----------------------------------------------------------------------------
 # Clip-weighted gradient (section 3, "DP gradient": a^T diag(C_1..C_B) dL/ds)
 # ----------------------------------------------------------------------------
@@ -215,6 +268,42 @@ def add_noise(grad_slice: np.ndarray, global_offset: int, sigma: float, R: float
 # Whole path on one micro-batch (section 3, flowchart: output gradient ->
 # clipping factor -> parameter gradient -> noising)
 # ----------------------------------------------------------------------------
+
+def private_gradient_grouped(layers, group_of_layer, R, mode: int, sigma: float, stability: float,
+                             seed: int, step: int, noise_offset: int, noise_count: int,
+                             with_bias: bool = False):
+    """Group-wise form of private_gradient (eq. (1), M groups).  With `with_bias`, every layer
+    also has a bias whose per-sample gradient 1^T g_i joins the layer's group; the flattened
+    result is then [W_0, b_0, W_1, b_1, ...].  Noise level sigma * ||R||_2 on the given range."""
+    L = len(layers)
+    B = layers[0][0].shape[0]
+    rows, row_group = [], []
+    for l, (a, g) in enumerate(layers):
+        path = choose_path(a.shape[1], a.shape[2], g.shape[2])
+        rows.append(ghost_sqnorm(a, g) if path == PATH_GHOST else perex_sqnorm(a, g))
+        row_group.append(group_of_layer[l])
+        if with_bias:
+            rows.append(bias_sqnorm(g))
+            row_group.append(group_of_layer[l])
+    sqn = np.stack(rows)
+    C, norm = clip_factors_grouped(sqn, row_group, R, mode, stability)
+    pieces, grads, bias_grads = [], [], []
+    for l, (a, g) in enumerate(layers):
+        G = clipped_grad(a, g, C[group_of_layer[l]])
+        grads.append(G)
+        pieces.append(G.reshape(-1))
+        if with_bias:
+            bgrad = clipped_bias_grad(g, C[group_of_layer[l]])
+            bias_grads.append(bgrad)
+            pieces.append(bgrad)
+    flat = np.concatenate(pieces).astype(np.float32)
+    if noise_count and sigma != 0:
+        std = group_noise_std(sigma, R)
+        sl = slice(noise_offset, noise_offset + noise_count)
+        z = normals(seed, step, noise_offset, noise_count)
+        flat[sl] = (flat[sl].astype(np.float64) + std * z).astype(np.float32)
+    return dict(sqnorm=sqn, C=C, norm=norm, grads=grads, bias_grads=bias_grads, flat=flat)
+
 
 def private_gradient(layers, mode: int, R: float, sigma: float, stability: float,
                      seed: int, step: int, noise_offset: int, noise_count: int,

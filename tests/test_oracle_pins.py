@@ -465,3 +465,88 @@ def test_synthetic_ranges_and_determinism():
     assert abs(g.std() / (1e-2 * s) - 1.0) < 0.01 and np.abs(g).max() < 1e1
     assert si.WORKLOADS["cfg4"].noise_range() == (0, 226492416)
     assert si.WORKLOADS["cfg1"].psi == 84934656 and si.WORKLOADS["cfg2"].psi == 707788800
+
+
+# ----------------------------------------------------------------------------
+# group-wise clipping (eq. (1) with M groups; section 2.1) and bias gradients (appendix A.1)
+# ----------------------------------------------------------------------------
+
+def test_grouped_clipping_one_group_is_all_layer():
+    rng = np.random.default_rng(21)
+    sqn = rng.uniform(0, 3, size=(4, 6))
+    for mode in (o.CLIP_STANDARD, o.CLIP_AUTOMATIC):
+        C1, n1 = o.clip_factors(sqn, mode, 1.3)
+        Cg, ng = o.clip_factors_grouped(sqn, [0, 0, 0, 0], [1.3], mode)
+        np.testing.assert_array_equal(Cg[0], C1)
+        np.testing.assert_array_equal(ng[0], n1)
+
+
+def test_grouped_clipping_hand_values():
+    # layers 0 and 2 form group 0 (9 + 16 -> norm 5), layer 1 is group 1 (norm 2)
+    sqn = np.array([[9.0], [4.0], [16.0]])
+    C, norm = o.clip_factors_grouped(sqn, [0, 1, 0], [1.0, 4.0], o.CLIP_STANDARD)
+    assert norm[0, 0] == 5.0 and norm[1, 0] == 2.0
+    assert C[0, 0] == 0.2 and C[1, 0] == 1.0           # group 1 is inside its ball (R = 4)
+    C, _ = o.clip_factors_grouped(sqn, [0, 1, 0], [1.0, 4.0], o.CLIP_AUTOMATIC)
+    assert C[0, 0] == pytest.approx(1 / 5.01) and C[1, 0] == pytest.approx(4 / 2.01)
+
+
+def test_layerwise_clipping_bounds_every_group():
+    # ||C_{m,i} g_{[m],i}|| <= R_m for every group m and sample i, from brute-force gradients
+    rng = np.random.default_rng(22)
+    B, T = 3, 4
+    dims = [(3, 4), (4, 2), (2, 5)]
+    layers = [(rng.standard_normal((B, T, d)), rng.standard_normal((B, T, p))) for d, p in dims]
+    R = [0.5, 2.0, 1e3]
+    res = o.private_gradient_grouped(layers, [0, 1, 2], R, o.CLIP_STANDARD, 0.0, 0.01, 0, 0, 0, 0)
+    for m, (a, g) in enumerate(layers):
+        for i in range(B):
+            n = math.sqrt(brute_sqnorm(a[i].tolist(), g[i].tolist()))
+            assert res["C"][m, i] * n <= R[m] * (1 + 1e-12)
+            np.testing.assert_allclose(res["norm"][m, i], n, rtol=1e-12)
+        assert np.all(res["C"][2] == 1.0)               # R = 1000: nothing clipped in group 2
+        want = sum(res["C"][m, i] * np.array(brute_per_sample_grad(a[i].tolist(), g[i].tolist())) for i in range(B))
+        np.testing.assert_allclose(res["grads"][m], want, rtol=1e-12, atol=1e-13)
+
+
+def test_group_noise_level():
+    assert o.group_noise_std(0.5, [3.0, 4.0]) == 2.5
+    assert o.group_noise_std(2.0, [1.5]) == 3.0
+    rng = np.random.default_rng(23)
+    layers = [(rng.standard_normal((2, 3, 64)), rng.standard_normal((2, 3, 512))) for _ in range(2)]
+    clean = o.private_gradient_grouped(layers, [0, 1], [3.0, 4.0], o.CLIP_STANDARD, 0.0, 0.01, 1, 0, 0, 65536)["flat"]
+    noisy = o.private_gradient_grouped(layers, [0, 1], [3.0, 4.0], o.CLIP_STANDARD, 0.5, 0.01, 1, 0, 0, 65536)["flat"]
+    delta = noisy.astype(np.float64) - clean
+    assert abs(delta.std() / 2.5 - 1) < 5 / math.sqrt(2 * 65536)
+    np.testing.assert_allclose(delta, 2.5 * o.normals(1, 0, 0, 65536), atol=1e-5)
+
+
+def test_bias_gradient_brute_force_and_closed_forms():
+    rng = np.random.default_rng(24)
+    g = rng.standard_normal((3, 5, 4))
+    want = np.array([[math.fsum(g[i, t, k] for t in range(5)) for k in range(4)] for i in range(3)])
+    np.testing.assert_allclose(o.bias_per_sample_grad(g), want, rtol=1e-14, atol=1e-15)
+    np.testing.assert_allclose(o.bias_sqnorm(g), np.sum(want ** 2, axis=1), rtol=1e-13)
+    # one token: the bias gradient is that row
+    np.testing.assert_array_equal(o.bias_per_sample_grad(g[:, :1]), g[:, 0])
+    # unit weights: the plain bias gradient, column sums over all B*T rows (library routine)
+    np.testing.assert_allclose(o.clipped_bias_grad(g, np.ones(3)), g.reshape(-1, 4).sum(axis=0), rtol=1e-13)
+    C = np.array([0.5, 0.0, 2.0])
+    np.testing.assert_allclose(o.clipped_bias_grad(g, C), 0.5 * want[0] + 2.0 * want[2], rtol=1e-13)
+    # rows that cancel: zero bias gradient whatever the weight gradient is
+    g2 = np.stack([np.concatenate([g[0], -g[0]])])
+    assert np.all(np.abs(o.bias_sqnorm(g2)) < 1e-28)
+
+
+def test_bias_joins_the_group_norm():
+    rng = np.random.default_rng(25)
+    B, T = 2, 3
+    layers = [(rng.standard_normal((B, T, 3)), rng.standard_normal((B, T, 4)))]
+    res = o.private_gradient_grouped(layers, [0], [1.0], o.CLIP_STANDARD, 0.0, 0.01, 0, 0, 0, 0, with_bias=True)
+    a, g = layers[0]
+    for i in range(B):
+        total = brute_sqnorm(a[i].tolist(), g[i].tolist()) + float(np.sum(g[i].sum(axis=0) ** 2))
+        np.testing.assert_allclose(res["norm"][0, i], math.sqrt(total), rtol=1e-12)
+        assert res["C"][0, i] * math.sqrt(total) <= 1.0 + 1e-12
+    assert res["flat"].size == 3 * 4 + 4
+    np.testing.assert_allclose(res["flat"][12:], res["bias_grads"][0], rtol=1e-6)
