@@ -173,6 +173,45 @@ dp_status dp_norms_multi(const dp_layer* layers, int L, dp_dtype dt, int B, floa
 dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
                                 float* const* grads, int accumulate, void* stream);
 
+/*
+ * Group-wise clipping (eq. (1) with M groups; section 2.1, "Mathematical gradient partition":
+ * all-layer clipping is one group, layer-wise clipping one group per layer, the paper's default).
+ * The rows of sqnorm (one per layer weight, plus one per bias when biases are trained) are
+ * partitioned into M contiguous groups: group m owns rows [group_begin[m], group_begin[m+1]) and
+ * has its own threshold R[m]:
+ *   norm_{m,i} = sqrt(max(0, sum of the group's rows at sample i)),  C_{m,i} = clip(norm_{m,i}; R[m]).
+ *   sqnorm       device, [L, B] fp32
+ *   group_begin  HOST, [M+1] ascending, group_begin[0] = 0, group_begin[M] = L (empty groups allowed)
+ *   R            HOST, [M], each > 0
+ *   C_out        device, [M, B] fp32;  norm_out device [M, B] or NULL
+ * dp_clipped_grad_grouped is dp_clipped_grad_multi with layer l weighted by row group_of_layer[l]
+ * (HOST, [L], values in [0, M)) of C [M, B].
+ * The noise of eq. (1) has standard deviation sigma * ||[R_1..R_M]||_2: pass
+ * dp_group_noise_threshold(R, M) as the R of dp_add_noise.
+ */
+dp_status dp_clip_factors_grouped(const float* sqnorm, int L, int B, const int32_t* group_begin, int M,
+                                  const float* R, dp_clip_mode mode, float stability, float* C_out,
+                                  float* norm_out, void* stream);
+dp_status dp_clipped_grad_grouped(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                  const int32_t* group_of_layer, int M, float* const* grads,
+                                  int accumulate, void* stream);
+float dp_group_noise_threshold(const float* R, int M);
+
+/*
+ * Bias gradients (appendix A.1, last paragraph): the per-sample bias gradient is 1^T dL/ds_i, the
+ * sum of sample i's T rows of g; its norm is taken by instantiation.
+ * dp_bias_norm:  colsum[i, k] = sum_t g[i, t, k]  and  sqnorm_out[i] = sum_k colsum[i, k]^2.
+ *   g           device, [B, T, d_out] of type dt (bf16: d_out a multiple of 8), 16-byte aligned
+ *   colsum      device, [B, d_out] fp32, overwritten; keep it for dp_clipped_bias_grad
+ *   sqnorm_out  device, [B] fp32, overwritten (use it as one more row of sqnorm)
+ * dp_clipped_bias_grad:  grad_b[k] (+)= sum_i C[i] * colsum[i, k]   (g is not read again).
+ *   C device [B];  grad_b device [d_out] fp32;  accumulate 0 or 1
+ */
+dp_status dp_bias_norm(const void* g, dp_dtype dt, int B, int T, int d_out, float* colsum,
+                       float* sqnorm_out, void* stream);
+dp_status dp_clipped_bias_grad(const float* colsum, int B, int d_out, const float* C, float* grad_b,
+                               int accumulate, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

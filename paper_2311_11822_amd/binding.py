@@ -43,6 +43,12 @@ _PROTOS = {
     "dp_norms_multi_workspace_bytes": (_sz, [C.POINTER(dp_layer), _i, _i, _i]),
     "dp_norms_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, _vp, _sz, _vp]),
     "dp_clipped_grad_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp), _i, _vp]),
+    "dp_clip_factors_grouped": (_i, [_vp, _i, _i, C.POINTER(C.c_int32), _i, C.POINTER(_f), _i, _f, _vp, _vp, _vp]),
+    "dp_clipped_grad_grouped": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(C.c_int32), _i,
+                                     C.POINTER(_vp), _i, _vp]),
+    "dp_group_noise_threshold": (_f, [C.POINTER(_f), _i]),
+    "dp_bias_norm": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp]),
+    "dp_clipped_bias_grad": (_i, [_vp, _i, _i, _vp, _vp, _i, _vp]),
 }
 EXPORTS = tuple(_PROTOS)
 for _name, (_res, _args) in _PROTOS.items():
@@ -146,3 +152,40 @@ def dp_clipped_grad_multi(layers, dt, B, Cf, grads, accumulate=0, stream=None) -
     gp = grads if isinstance(grads, C.Array) else (C.c_void_p * len(grads))(*[_ptr(x) for x in grads])
     _check(lib.dp_clipped_grad_multi(arr, len(arr), dt, B, _ptr(Cf), gp, accumulate, _stream(stream)),
            "dp_clipped_grad_multi")
+
+
+def _i32(xs):
+    return (C.c_int32 * len(xs))(*xs)
+
+
+def _f32(xs):
+    return (C.c_float * len(xs))(*xs)
+
+
+def dp_clip_factors_grouped(sqnorm, L, B, group_begin, R, mode, stability, C_out, norm_out=None,
+                            stream=None) -> None:
+    M = len(R)
+    _check(lib.dp_clip_factors_grouped(_ptr(sqnorm), L, B, _i32(group_begin), M, _f32(R), mode, stability,
+                                       _ptr(C_out), _ptr(norm_out), _stream(stream)),
+           "dp_clip_factors_grouped")
+
+
+def dp_clipped_grad_grouped(layers, dt, B, Cf, group_of_layer, M, grads, accumulate=0, stream=None) -> None:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    gp = grads if isinstance(grads, C.Array) else (C.c_void_p * len(grads))(*[_ptr(x) for x in grads])
+    _check(lib.dp_clipped_grad_grouped(arr, len(arr), dt, B, _ptr(Cf), _i32(group_of_layer), M, gp, accumulate,
+                                       _stream(stream)), "dp_clipped_grad_grouped")
+
+
+def dp_group_noise_threshold(R) -> float:
+    return lib.dp_group_noise_threshold(_f32(R), len(R))
+
+
+def dp_bias_norm(g, dt, B, T, d_out, colsum, sqnorm_out, stream=None) -> None:
+    _check(lib.dp_bias_norm(_ptr(g), dt, B, T, d_out, _ptr(colsum), _ptr(sqnorm_out), _stream(stream)),
+           "dp_bias_norm")
+
+
+def dp_clipped_bias_grad(colsum, B, d_out, Cf, grad_b, accumulate=0, stream=None) -> None:
+    _check(lib.dp_clipped_bias_grad(_ptr(colsum), B, d_out, _ptr(Cf), _ptr(grad_b), accumulate, _stream(stream)),
+           "dp_clipped_bias_grad")

@@ -63,6 +63,7 @@ dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, const std::ve
       gl.sq_index = l;
       gl.part_begin = (int)part_begin[l];
       gl.tiles_per_sample = tiles_per_sample(gl.path, layers[l]);
+      gl.c_off = 0;
       blocks += (int64_t)gl.tiles_per_sample * B;
     }
     ga.total_blocks = (int)blocks;
@@ -204,8 +205,14 @@ dp_status dp_clip_factors(const float* sqnorm, int L, int B, dp_clip_mode mode, 
                              static_cast<hipStream_t>(stream));
 }
 
-dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
-                                float* const* grads, int accumulate, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Clip-weighted gradients of a stack; layer l uses the weights C[c_off[l] + i] (c_off == nullptr:
+// every layer uses C[i]).
+dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                            const int* c_off, float* const* grads, int accumulate, void* stream) {
   if (dt != DP_F32 && dt != DP_BF16) return DP_ERR_INVALID_ARG;
   if (!layers || !grads || !C || L <= 0 || B <= 0) return DP_ERR_INVALID_ARG;
   if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
@@ -221,7 +228,8 @@ dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int 
     for (int l = 0; l < L; ++l) {
       dp_status st = launch_clipped_grad_f32(static_cast<const float*>(layers[l].a),
                                              static_cast<const float*>(layers[l].g), B, layers[l].T,
-                                             layers[l].d_in, layers[l].d_out, C, grads[l], accumulate, s);
+                                             layers[l].d_in, layers[l].d_out, C + (c_off ? c_off[l] : 0),
+                                             grads[l], accumulate, s);
       if (st != DP_OK) return st;
     }
     return DP_OK;
@@ -260,6 +268,7 @@ dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int 
         gl.sq_index = l;
         gl.part_begin = 0;
         gl.tiles_per_sample = (int)tiles;
+        gl.c_off = c_off ? c_off[l] : 0;
         blocks += tiles;
         ++pos;
       }
@@ -269,6 +278,65 @@ dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int 
     }
   }
   return DP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                float* const* grads, int accumulate, void* stream) {
+  return clipped_grad_impl(layers, L, dt, B, C, nullptr, grads, accumulate, stream);
+}
+
+dp_status dp_clipped_grad_grouped(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                  const int32_t* group_of_layer, int M, float* const* grads,
+                                  int accumulate, void* stream) {
+  if (!group_of_layer || L <= 0 || M <= 0 || B <= 0 || (int64_t)M * B > INT32_MAX) return DP_ERR_INVALID_ARG;
+  std::vector<int> c_off(L);
+  for (int l = 0; l < L; ++l) {
+    if (group_of_layer[l] < 0 || group_of_layer[l] >= M) return DP_ERR_INVALID_ARG;
+    c_off[l] = group_of_layer[l] * B;
+  }
+  return clipped_grad_impl(layers, L, dt, B, C, c_off.data(), grads, accumulate, stream);
+}
+
+dp_status dp_clip_factors_grouped(const float* sqnorm, int L, int B, const int32_t* group_begin, int M,
+                                  const float* R, dp_clip_mode mode, float stability, float* C_out,
+                                  float* norm_out, void* stream) {
+  if (!sqnorm || !C_out || !group_begin || !R || L <= 0 || B <= 0 || M <= 0) return DP_ERR_INVALID_ARG;
+  if (mode != DP_CLIP_STANDARD && mode != DP_CLIP_AUTOMATIC) return DP_ERR_INVALID_ARG;
+  if (!(stability >= 0.f) || isinf(stability)) return DP_ERR_INVALID_ARG;
+  if (group_begin[0] != 0 || group_begin[M] != L) return DP_ERR_INVALID_ARG;
+  for (int m = 0; m < M; ++m) {
+    if (group_begin[m + 1] < group_begin[m]) return DP_ERR_INVALID_ARG;     // empty groups are allowed
+    if (!(R[m] > 0.f)) return DP_ERR_INVALID_ARG;
+  }
+  return launch_clip_factors_grouped(sqnorm, B, group_begin, M, R, (int)mode, stability, C_out, norm_out,
+                                     static_cast<hipStream_t>(stream));
+}
+
+float dp_group_noise_threshold(const float* R, int M) {
+  if (!R || M <= 0) return 0.f;
+  double s = 0.0;
+  for (int m = 0; m < M; ++m) s += (double)R[m] * R[m];
+  return (float)sqrt(s);
+}
+
+dp_status dp_bias_norm(const void* g, dp_dtype dt, int B, int T, int d_out, float* colsum,
+                       float* sqnorm_out, void* stream) {
+  if (dt != DP_F32 && dt != DP_BF16) return DP_ERR_INVALID_ARG;
+  if (!g || !colsum || !sqnorm_out || !aligned16(g)) return DP_ERR_INVALID_ARG;
+  if (!dims_ok(dt, B, T, 8, d_out)) return DP_ERR_INVALID_ARG;
+  if (B > 65535) return DP_ERR_UNSUPPORTED;
+  return launch_bias_norm(g, dt == DP_BF16, B, T, d_out, colsum, sqnorm_out, static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_clipped_bias_grad(const float* colsum, int B, int d_out, const float* C, float* grad_b,
+                               int accumulate, void* stream) {
+  if (!colsum || !C || !grad_b || B <= 0 || d_out <= 0) return DP_ERR_INVALID_ARG;
+  if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
+  return launch_clipped_bias_grad(colsum, B, d_out, C, grad_b, accumulate, static_cast<hipStream_t>(stream));
 }
 
 dp_status dp_clipped_grad(const void* a, const void* g, dp_dtype dt, int B, int T, int d_in, int d_out,

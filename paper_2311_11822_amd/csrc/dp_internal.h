@@ -28,6 +28,7 @@ struct GroupLayer {
   int sq_index;     // layer number within the caller's stack (row of sqnorm)
   int part_begin;   // first partial-sum slot of this layer in the workspace
   int tiles_per_sample;
+  int c_off;        // gradient kernels: this layer's weights are C[c_off + i] (its clipping group)
 };
 
 struct GroupArgs {
@@ -47,6 +48,13 @@ dp_status launch_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_b
                                uint64_t seed, uint64_t step, hipStream_t s);
 dp_status launch_clip_factors(const float* sqnorm, int L, int B, int mode, float R, float stability,
                               float* C_out, float* norm_out, hipStream_t s);
+dp_status launch_clip_factors_grouped(const float* sqnorm, int B, const int32_t* group_begin, int M,
+                                      const float* R, int mode, float stability, float* C_out,
+                                      float* norm_out, hipStream_t s);
+dp_status launch_bias_norm(const void* g, int is_bf16, int B, int T, int p, float* colsum,
+                           float* sqnorm_out, hipStream_t s);
+dp_status launch_clipped_bias_grad(const float* colsum, int B, int p, const float* C, float* grad_b,
+                                   int accumulate, hipStream_t s);
 
 dp_status launch_ghost_f32(const float* a, const float* g, int B, int T, int d, int p, float* out,
                            hipStream_t s);

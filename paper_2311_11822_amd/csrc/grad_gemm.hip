@@ -137,6 +137,7 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) 
   const int T = ly.T, d = ly.d_in, p = ly.d_out;
   const int B = ga.B;
   const int nkb = (T + BK - 1) / BK;
+  C += ly.c_off;                                  // the layer's clipping group
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: keeps LDS bases scalar

@@ -154,13 +154,14 @@ __device__ __forceinline__ int find_layer(const GroupArgs& ga, int block) {
 // ---------------------------------------------------------------------------------
 template <class S>
 __global__ void __launch_bounds__(S::NT)
-clipped_grad_kernel(const GroupArgs ga, const float* __restrict__ C) {
+clipped_grad_kernel(const GroupArgs ga, const float* __restrict__ C_all) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   const int l = find_layer(ga, blockIdx.x);
   const GroupLayer& ly = ga.layer[l];
   const int local = blockIdx.x - ly.tile_begin;
   const int tiles_n = (ly.d_out + S::BN - 1) / S::BN;
   const int B = ga.B;
+  const float* __restrict__ C = C_all + ly.c_off;      // the layer's clipping group
 
   TnTile<S> t;
   t.a = static_cast<const uint16_t*>(ly.a);

@@ -371,6 +371,107 @@ def test_cfg4_wide_block_shard(dp, Pipe):
 
 
 # ----------------------------------------------------------------------------
+# group-wise clipping (eq. (1), M groups) and bias gradients (appendix A.1)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_grouped_clip_factors(dp, mode):
+    rng = np.random.default_rng(31)
+    L, B = 11, 37
+    sqn = rng.uniform(0, 2, size=(L, B)).astype(np.float32)
+    begin = [0, 3, 3, 4, 11]                          # group 1 is empty
+    R = [0.5, 1.0, 2.0, 1e3]
+    group_of_row = [0, 0, 0, 2, 3, 3, 3, 3, 3, 3, 3]
+    Cd = torch.zeros((4, B), dtype=torch.float32, device="cuda")
+    nd = torch.zeros((4, B), dtype=torch.float32, device="cuda")
+    dp.dp_clip_factors_grouped(dev(sqn), L, B, begin, R, mode, 0.01, Cd, nd)
+    C, norm = o.clip_factors_grouped(sqn.astype(np.float64), group_of_row, R, mode, 0.01)
+    np.testing.assert_allclose(host(nd), norm, rtol=TOL_F32, atol=1e-30)
+    np.testing.assert_allclose(host(Cd), C, rtol=TOL_F32)
+    assert dp.dp_group_noise_threshold([3.0, 4.0]) == 5.0
+
+
+@pytest.mark.parametrize("dtype,B,T,p", [(si.F32, 3, 5, 7), (si.BF16, 2, 300, 520), (si.BF16, 8, 512, 5120),
+                                         (si.BF16, 1, 1, 8), (si.F32, 4, 8, 16)])
+def test_bias_norm_and_clipped_bias_grad(dp, dtype, B, T, p):
+    w = si.small_workload("bias", dtype, B, T, [(8, p)])
+    g = si.gen_tensor(w, 0, 1)
+    g64 = si.to_f64(g)
+    dt = dp.DP_F32 if dtype == si.F32 else dp.DP_BF16
+    colsum = torch.full((B, p), -1.0, dtype=torch.float32, device="cuda")
+    sq = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
+    dp.dp_bias_norm(dev(g), dt, B, T, p, colsum, sq)
+    tol = TOL_F32 if dtype == si.F32 else TOL_BF16_NORM
+    assert frob(host(colsum), o.bias_per_sample_grad(g64)) <= 1e-5
+    assert rel(host(sq), o.bias_sqnorm(g64)) <= tol
+    C = np.random.default_rng(4).uniform(0, 1, B).astype(np.float32)
+    C[0] = 0.0
+    gb = torch.full((p,), 2.0, dtype=torch.float32, device="cuda")
+    dp.dp_clipped_bias_grad(colsum, B, p, dev(C), gb, 0)
+    want = o.clipped_bias_grad(g64, C.astype(np.float64))
+    assert frob(host(gb), want) <= 1e-5 or np.linalg.norm(want) == 0
+    dp.dp_clipped_bias_grad(colsum, B, p, dev(C), gb, 1)
+    assert frob(host(gb), 2 * want) <= 1e-5 or np.linalg.norm(want) == 0
+
+
+@pytest.mark.parametrize("dtype", [si.F32, si.BF16])
+def test_layerwise_clipping_with_biases(dp, dtype):
+    # The paper's default setting: one clipping group per layer (weight + bias), noise level
+    # sigma * ||R||_2; flattened result [W_0, b_0, W_1, b_1, ...].
+    dims = [(72, 264), (264, 136), (136, 16)] if dtype == si.BF16 else [(4, 8), (8, 4), (4, 12)]
+    B, T = (3, 150) if dtype == si.BF16 else (4, 6)
+    w = si.small_workload("lw", dtype, B, T, dims, g_std=1e-2 if dtype == si.BF16 else 1.0)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    dt = dp.DP_F32 if dtype == si.F32 else dp.DP_BF16
+    L, M = len(dims), len(dims)
+    R = [0.05, 0.2, 1e3]
+    sigma = 0.3
+    dlayers = [(dev(a), dev(g)) for a, g in layers]
+    # rows of sqnorm: W_0, b_0, W_1, b_1, ...
+    sqn = torch.zeros((2 * L, B), dtype=torch.float32, device="cuda")
+    colsums, paths = [], []
+    for l, ((a, g), (d, p)) in enumerate(zip(dlayers, dims)):
+        path = dp.dp_choose_path(T, d, p)
+        paths.append(path)
+        nbytes = dp.dp_norm_workspace_bytes(path, dt, B, T, d, p)
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+        fn = dp.dp_ghost_norm if path == dp.DP_PATH_GHOST else dp.dp_perex_norm
+        fn(a, g, dt, B, T, d, p, sqn[2 * l], ws)
+        cs = torch.zeros((B, p), dtype=torch.float32, device="cuda")
+        dp.dp_bias_norm(g, dt, B, T, p, cs, sqn[2 * l + 1])
+        colsums.append(cs)
+    Cd = torch.zeros((M, B), dtype=torch.float32, device="cuda")
+    dp.dp_clip_factors_grouped(sqn, 2 * L, B, [0, 2, 4, 6], R, dp.DP_CLIP_STANDARD, 0.01, Cd)
+    psi = sum(d * p + p for d, p in dims)
+    flat = torch.zeros(psi, dtype=torch.float32, device="cuda")
+    wg, bg, off = [], [], 0
+    for d, p in dims:
+        wg.append(flat[off:off + d * p].view(d, p))
+        off += d * p
+        bg.append(flat[off:off + p])
+        off += p
+    desc = [(a, g, T, d, p, path) for (a, g), (d, p), path in zip(dlayers, dims, paths)]
+    if any(x.data_ptr() % 16 for x in wg):
+        pytest.skip("flattened layout not 16-byte aligned for this shape")
+    dp.dp_clipped_grad_grouped(desc, dt, B, Cd, [0, 1, 2], M, wg, 0)
+    for l, (d, p) in enumerate(dims):
+        dp.dp_clipped_bias_grad(colsums[l], B, p, Cd[l], bg[l], 0)
+    ref = o.private_gradient_grouped(l64, [0, 1, 2], R, o.CLIP_STANDARD, 0.0, 0.01, 1, 0, 0, 0, with_bias=True)
+    tol = TOL_F32 if dtype == si.F32 else TOL_BF16_NORM
+    assert rel(host(sqn), ref["sqnorm"]) <= tol
+    assert rel(host(Cd), ref["C"]) <= tol
+    assert np.all(host(Cd)[2] == 1.0) and np.all(host(Cd)[0] < 1.0)
+    assert frob(host(flat), ref["flat"]) <= (1e-5 if dtype == si.F32 else 1e-4)
+    clean = host(flat).copy()
+    thr = dp.dp_group_noise_threshold(R)
+    dp.dp_add_noise(flat, 0, psi, sigma, thr, 1, 0)
+    z = (host(flat).astype(np.float64) - clean) / o.group_noise_std(sigma, R)
+    want = o.normals(1, 0, 0, psi)
+    assert np.all(np.abs(z - want) <= 2e-5 * np.maximum(1.0, np.abs(want)))
+
+
+# ----------------------------------------------------------------------------
 # error paths: every refusal happens on the host, nothing is launched
 # ----------------------------------------------------------------------------
 
