@@ -80,10 +80,19 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   const unsigned lds0 = (unsigned)(uintptr_t)lds_raw;
 
+  // XCD-aware order.  Workgroup b runs on XCD b % 8 (round-robin dispatch); the tiles of one
+  // sample read the same token rows, so each XCD takes one contiguous range of tile numbers
+  // and a sample's tiles meet in one L2 instead of being fetched by up to eight.
+  int logical;
+  {
+    const int n = ga.total_blocks, per = n >> 3, rest = n & 7;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    logical = xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx;
+  }
   int l = 0;
-  while (l + 1 < ga.n_layers && (int)blockIdx.x >= ga.layer[l + 1].tile_begin) ++l;
+  while (l + 1 < ga.n_layers && logical >= ga.layer[l + 1].tile_begin) ++l;
   const GroupLayer& ly = ga.layer[l];
-  const int local = blockIdx.x - ly.tile_begin;
+  const int local = logical - ly.tile_begin;
   const int sample = local / ly.tiles_per_sample;
   int q = local % ly.tiles_per_sample;
   const int T = ly.T;
