@@ -26,6 +26,7 @@
 #include <type_traits>
 
 #include "dp_internal.h"
+#include "tn_tile.h"
 
 namespace dpbk {
 
@@ -374,6 +375,200 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) 
     store_tile(std::false_type{});
 }
 
+
+// ---------------------------------------------------------------------------------
+// Tail of a launch.  All tiles of a launch take the same time and one workgroup fills a compute
+// unit, so n tiles run in ceil(n / 256) rounds; when the last round would hold only a few tiles
+// (n mod 256 small), those tiles are cut into TAIL x TAIL sub-tiles instead, one small
+// workgroup each (register-staged tile code of tn_tile.h), which spreads them over the whole
+// chip.  Sub-tile b of the launch belongs to tile first_tile + b / SUBS of locate_tile's order.
+// ---------------------------------------------------------------------------------
+#ifndef DP_TAIL_SHAPE
+#define DP_TAIL_SHAPE 64, 64, 64, 2, 2
+#endif
+#ifndef DP_TAIL_DEPTH
+#define DP_TAIL_DEPTH 4
+#endif
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+// One small output tile with D k-blocks in flight between memory and LDS (register slots used
+// in rotation, the loop unrolled D times so that every slot index is a constant).  A small
+// tile's k-block holds too little arithmetic to cover the latency of the next one's loads,
+// and with one wave per SIMD every instruction of the loop counts: the loads are buffer loads
+// whose range check zero-fills what lies outside the sample's slab (rows past T, columns past
+// the layer's edge through the OOB offset, blocks past the last sample through an empty
+// descriptor), so a k-block costs one add and one load per 16 bytes and nothing is
+// conditional: the number of loads in flight is a compile-time constant and a thread waits only
+// for the slot it is about to store.  Two LDS stages, one barrier per k-block.  The k-steps of an output element are added in
+// the same order as in the large kernel.
+template <class S, int D>
+__device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int B, int accumulate,
+                                                       int m0, int n0,
+                                                       const __attribute__((address_space(4))) float* C,
+                                                       uint16_t* lds) {
+  static_assert(D % 2 == 0, "the LDS stage of slot q is q & 1");
+  const int tid = threadIdx.x;
+  const int T = ly.T, d = ly.d_in, p = ly.d_out;
+  const int nkb = (T + S::BK - 1) / S::BK;
+  const unsigned a_slab = (unsigned)T * d * 2u, b_slab = (unsigned)T * p * 2u;
+  const unsigned a_step = (unsigned)S::BK * d * 2u, b_step = (unsigned)S::BK * p * 2u;
+  const unsigned char* a_base = static_cast<const unsigned char*>(ly.a);
+  const unsigned char* b_base = static_cast<const unsigned char*>(ly.g);
+
+  // Per-thread geometry of the loads of one k-block: byte offset inside the slab (k-block 0)
+  // and element offset inside the LDS stage.
+  unsigned va[S::A_PER_T], vb[S::B_PER_T];
+  int sta[S::A_PER_T], stb[S::B_PER_T];
+#pragma unroll
+  for (int j = 0; j < S::A_PER_T; ++j) {
+    const int c = tid + j * S::NT, row = c / (S::BM / 8), col = (c % (S::BM / 8)) * 8;
+    va[j] = m0 + col < d ? (unsigned)(row * d + m0 + col) * 2u : OOB;
+    sta[j] = row * S::SA + col;
+  }
+#pragma unroll
+  for (int j = 0; j < S::B_PER_T; ++j) {
+    const int c = tid + j * S::NT, row = c / (S::BN / 8), col = (c % (S::BN / 8)) * 8;
+    vb[j] = n0 + col < p ? (unsigned)(row * p + n0 + col) * 2u : OOB;
+    stb[j] = S::BK * S::SA + row * S::SB + col;
+  }
+
+  // All operand fragments of a k-block are requested from LDS before its first MFMA, so one LDS
+  // latency is exposed per k-block instead of one per MFMA (a wave has nothing else to run).
+  static_assert(S::TM == 1 && S::TN == 1, "one 32 x 32 MFMA tile per wave");
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave / S::WN) * S::WTM, wn = (wave % S::WN) * S::WTN;
+  auto compute = [&](const uint16_t* stage, f32x16& c) {
+    constexpr int KS = S::BK / 16;
+    bf16x8 fa[KS], fb[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fa[ks] = read_frag_tr(stage, S::SA, ks * 16, wm, lane);
+      fb[ks] = read_frag_tr(stage + S::BK * S::SA, S::SB, ks * 16, wn, lane);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fb[ks], c, 0, 0, 0);
+  };
+  u32x4 sa[D][S::A_PER_T], sb[D][S::B_PER_T];
+  f32x16 acc[S::TM][S::TN];
+  zero_acc<S>(acc);
+
+  // (sample, k-block) cursors over the samples with a non-zero weight: ld = next block to
+  // request from memory, cp = next block to compute.
+  int ld_i = 0, ld_kb = 0, cp_i, cp_kb = 0, active = 0;
+  for (int i = 0; i < B; ++i) active += C[i] != 0.f;
+  while (ld_i < B && C[ld_i] == 0.f) ++ld_i;
+  cp_i = ld_i;
+  float held = cp_i < B ? C[cp_i] : 0.f;   // weight the accumulator is currently expressed in
+  __amdgpu_buffer_rsrc_t ra, rb;
+  unsigned koff_a = 0, koff_b = 0;         // byte offset of the load cursor's k-block in the slab
+  auto open_sample = [&]() {
+    const bool valid = ld_i < B;
+    const int smp = valid ? ld_i : 0;
+    ra = __builtin_amdgcn_make_buffer_rsrc((void*)(a_base + (size_t)smp * a_slab), 0,
+                                           valid ? (int)a_slab : 0, 0x00020000);
+    rb = __builtin_amdgcn_make_buffer_rsrc((void*)(b_base + (size_t)smp * b_slab), 0,
+                                           valid ? (int)b_slab : 0, 0x00020000);
+    koff_a = 0;
+    koff_b = 0;
+  };
+  open_sample();
+  auto fetch = [&](u32x4 (&xa)[S::A_PER_T], u32x4 (&xb)[S::B_PER_T]) {
+#pragma unroll
+    for (int j = 0; j < S::A_PER_T; ++j)
+      xa[j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, va[j] + koff_a, 0, 0));
+#pragma unroll
+    for (int j = 0; j < S::B_PER_T; ++j)
+      xb[j] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, vb[j] + koff_b, 0, 0));
+    koff_a += a_step;
+    koff_b += b_step;
+    if (ld_i < B && ++ld_kb == nkb) {
+      ld_kb = 0;
+      ++ld_i;
+      while (ld_i < B && C[ld_i] == 0.f) ++ld_i;
+      open_sample();
+    }
+  };
+#pragma unroll
+  for (int q = 0; q < D; ++q) fetch(sa[q], sb[q]);
+  auto store = [&](uint16_t* stage, const u32x4 (&xa)[S::A_PER_T], const u32x4 (&xb)[S::B_PER_T]) {
+#pragma unroll
+    for (int j = 0; j < S::A_PER_T; ++j) *reinterpret_cast<u32x4*>(stage + sta[j]) = xa[j];
+#pragma unroll
+    for (int j = 0; j < S::B_PER_T; ++j) *reinterpret_cast<u32x4*>(stage + stb[j]) = xb[j];
+  };
+  // Block n is computed from stage n & 1 while block n + 1 is being written to the other stage;
+  // the barrier at the end of an iteration certifies both that write and that nobody still
+  // reads the stage the next iteration overwrites.
+  const int blocks = active * nkb;
+  store(lds, sa[0], sb[0]);
+  fetch(sa[0], sb[0]);
+  __syncthreads();
+  for (int n = 0; n < blocks; n += D) {
+#pragma unroll
+    for (int q = 0; q < D; ++q) {
+      const int nq = (q + 1) % D;
+      store(lds + ((q + 1) & 1) * S::STAGE, sa[nq], sb[nq]);
+      fetch(sa[nq], sb[nq]);
+      compute(lds + (q & 1) * S::STAGE, acc[0][0]);
+      __syncthreads();
+      if (cp_i < B && ++cp_kb == nkb) {
+        cp_kb = 0;
+        ++cp_i;
+        while (cp_i < B && C[cp_i] == 0.f) ++cp_i;
+        if (cp_i < B) {                   // next block starts another sample: re-express acc
+          const float c = C[cp_i];
+          scale_acc<S>(acc, held / c);
+          held = c;
+        }
+      }
+    }
+  }
+
+  float* out = ly.out;
+#pragma unroll
+  for (int im = 0; im < S::TM; ++im)
+#pragma unroll
+    for (int jn = 0; jn < S::TN; ++jn) {
+      const int col = n0 + wn + jn * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm + im * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < d && col < p) {
+          float* dst = out + (size_t)row * p + col;
+          const float v = acc[im][jn][r] * held;
+          *dst = accumulate ? *dst + v : v;
+        }
+      }
+    }
+}
+
+// Sub-tiles are 64 x 64 (16 per tile), k-blocks of 64 rows, four k-blocks in flight: three
+// workgroups fit in a compute unit's LDS.
+using TailShape = TnShape<DP_TAIL_SHAPE>;
+constexpr int TAIL = 64, SUBS_N = BN / TAIL, SUBS = (BM / TAIL) * SUBS_N;
+static_assert(TailShape::BM == TAIL && TailShape::BN == TAIL, "sub-tile shape");
+
+__global__ void __launch_bounds__(TailShape::NT)
+clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, int first_tile) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_tail[];
+  // Workgroup b runs on XCD b % 8: give each XCD a contiguous eighth of the sub-tiles (the grid
+  // is a multiple of 16), so that the 16 sub-tiles of a tile, which share its operand panels,
+  // meet in one L2.
+  const int logical = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  int l, m0, n0;
+  locate_tile(ga, first_tile + logical / SUBS, l, m0, n0);
+  const GroupLayer& ly = ga.layer[l];
+  const int sub = logical % SUBS;
+  m0 += (sub / SUBS_N) * TAIL;
+  n0 += (sub % SUBS_N) * TAIL;
+  if (m0 >= ly.d_in || n0 >= ly.d_out) return;       // sub-tile past the layer's edge (whole workgroup)
+  const __attribute__((address_space(4))) float* C =
+      (const __attribute__((address_space(4))) float*)(uintptr_t)(C_all + ly.c_off);
+  clipped_grad_tile_deep<TailShape, DP_TAIL_DEPTH>(ly, ga.B, ga.accumulate, m0, n0, C, lds_tail);
+}
+
 }  // namespace
 
 int clipped_grad_big_tiles(int d, int p) { return ((d + BM - 1) / BM) * ((p + BN - 1) / BN); }
@@ -385,6 +580,16 @@ bool clipped_grad_big_supports(int T, int d, int p) {
   return T % BK == 0 && (int64_t)T * d * 2 < (int64_t)1 << 31 && (int64_t)T * p * 2 < (int64_t)1 << 31;
 }
 
+// Tiles left for the tail kernel: the last n mod 256 tiles of the launch when they are few.
+// Sub-tiles fetch four times the operand bytes per flop of a large tile and the tail kernel runs
+// at the rate the L2 delivers them (measured: 16 tiles with K = 4096 take 30-50 us, a round of
+// large tiles 150 us; 36 tiles about 0.7 of a round), so beyond kTailMax tiles a short last
+// round of large tiles is as fast.
+#ifndef DP_TAIL_MAX
+#define DP_TAIL_MAX 40
+#endif
+constexpr int kRound = 256;           // compute units = large-tile workgroups resident at a time
+
 dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, hipStream_t s) {
   static bool ready = false;
   if (!ready) {
@@ -392,9 +597,25 @@ dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, hip
                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
                                                   LDS_BYTES));
     if (st != DP_OK) return st;
+    st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(clipped_grad_tail_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)TailShape::LDS_BYTES));
+    if (st != DP_OK) return st;
     ready = true;
   }
-  hipLaunchKernelGGL(clipped_grad_big_kernel, dim3(ga.total_blocks), dim3(NT), LDS_BYTES, s, ga, C);
+  const int n = ga.total_blocks;
+  int n_tail = n % kRound;
+  if (n_tail > DP_TAIL_MAX) n_tail = 0;
+  if (n > n_tail) {
+    GroupArgs main_args = ga;
+    main_args.total_blocks = n - n_tail;
+    hipLaunchKernelGGL(clipped_grad_big_kernel, dim3(n - n_tail), dim3(NT), LDS_BYTES, s, main_args, C);
+    dp_status st = hip_status(hipGetLastError());
+    if (st != DP_OK) return st;
+  }
+  if (n_tail == 0) return DP_OK;
+  hipLaunchKernelGGL(clipped_grad_tail_kernel, dim3(n_tail * SUBS), dim3(TailShape::NT),
+                     TailShape::LDS_BYTES, s, ga, C, n - n_tail);
   return hip_status(hipGetLastError());
 }
 

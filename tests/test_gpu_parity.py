@@ -303,6 +303,11 @@ def sampled_grad_check(w, layers, C, pipe, full_layers=(), n_samples=2048, seed=
         if l in full_layers:
             G = o.clipped_grad(si.to_f64(a), si.to_f64(g), C)
             worst = max(worst, frob(host(got), G))
+            # every 64 x 64 block on its own too: the smallest unit one workgroup writes
+            have = host(got).astype(np.float64)
+            for r0 in range(0, d, 64):
+                for c0 in range(0, p, 64):
+                    worst = max(worst, frob(have[r0:r0 + 64, c0:c0 + 64], G[r0:r0 + 64, c0:c0 + 64]))
             continue
         rows = np.concatenate([rng.integers(0, d, n_samples), [0, 0, d - 1, d - 1]])
         cols = np.concatenate([rng.integers(0, p, n_samples), [0, p - 1, 0, p - 1]])
@@ -354,7 +359,8 @@ def run_workload(dp, Pipe, name, full_layers=()):
 
 
 def test_cfg1_gpt2_small_full(dp, Pipe):
-    run_workload(dp, Pipe, "cfg1", full_layers=(0, 1, 2, 3))
+    # layer 47 holds the launch's last tiles, which the sub-tile kernel computes
+    run_workload(dp, Pipe, "cfg1", full_layers=(0, 1, 2, 3, 47))
 
 
 def test_cfg3_long_sequence_full(dp, Pipe):
@@ -363,7 +369,8 @@ def test_cfg3_long_sequence_full(dp, Pipe):
 
 
 def test_cfg2_gpt2_large_full(dp, Pipe):
-    run_workload(dp, Pipe, "cfg2")
+    # the last layer of each launch of 48 holds the tiles the sub-tile kernel computes
+    run_workload(dp, Pipe, "cfg2", full_layers=(47, 95, 143))
 
 
 def test_cfg4_wide_block_shard(dp, Pipe):
