@@ -126,13 +126,17 @@ def main():
     norm_flops, grad_flops = workload_flops(w)
     grad_launches = -(-w.L // 48) if w.dtype == si.BF16 else w.L
     grad_tflops = grad_flops / (ms_grad * 1e-3) / 1e12
-    # HBM-side bytes per launch of the dominant kernel, from the committed rocprofv3 counter runs
+    # The gradient of one group of up to 48 layers is one launch of clipped_grad_big_kernel plus,
+    # when the last round of tiles is nearly empty, one of clipped_grad_tail_kernel for those
+    # tiles; "launch" below means that pair, timed together by the events around the stage.
+    # HBM-side bytes per launch from the committed rocprofv3 counter runs
     # (profiles/<workload>_all_kernels.md); null when this workload has not been profiled.
     traffic = None
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-            t = json.load(f)["per_launch"][w.name]["clipped_grad_big_kernel"]
-        traffic = t["fetch_bytes"] + t["write_bytes"]
+            per = json.load(f)["per_launch"][w.name]
+        traffic = sum(per[k]["fetch_bytes"] + per[k]["write_bytes"]
+                      for k in ("clipped_grad_big_kernel", "clipped_grad_tail_kernel") if k in per)
     except (OSError, KeyError, ValueError):
         pass
     out = {
@@ -151,7 +155,8 @@ def main():
         "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
         "noise_gbps": 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
-        "roofline": {"kernel": "clipped_grad_big_kernel" if w.dtype == si.BF16 else "clipped_grad_f32_kernel",
+        "roofline": {"kernel": "clipped_grad_big_kernel (+ clipped_grad_tail_kernel)" if w.dtype == si.BF16
+                     else "clipped_grad_f32_kernel",
                      "bound": "mfma",
                      "achieved": grad_tflops, "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
                      "frac": grad_tflops * 1e12 / PEAK_BF16_FLOPS,

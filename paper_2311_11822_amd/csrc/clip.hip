@@ -6,13 +6,23 @@ namespace dpbk {
 
 namespace {
 
-__global__ void __launch_bounds__(256)
+// Sum of rows [l0, l1) of sqnorm at column i, by one wave: each lane adds a strided subset in
+// order, then a fixed butterfly, so the result is deterministic; the rows are loaded in
+// parallel (a serial loop would pay one memory latency per layer).
+__device__ __forceinline__ float column_sum(const float* __restrict__ sqnorm, int B, int i, int l0, int l1) {
+  float total = 0.f;
+  for (int l = l0 + (int)threadIdx.x; l < l1; l += 64) total += sqnorm[(size_t)l * B + i];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off);
+  return total;
+}
+
+__global__ void __launch_bounds__(64)
 clip_factor_kernel(const float* __restrict__ sqnorm, int L, int B, int mode, float R,
                    float stability, float* __restrict__ C_out, float* __restrict__ norm_out) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B) return;
-  float total = 0.f;
-  for (int l = 0; l < L; ++l) total += sqnorm[(size_t)l * B + i];   // fixed order: deterministic
+  const int i = blockIdx.x;                                  // one wave per sample
+  const float total = column_sum(sqnorm, B, i, 0, L);
+  if (threadIdx.x != 0) return;
   const float norm = __builtin_sqrtf(fmaxf(total, 0.f));
   float c;
   if (mode == DP_CLIP_STANDARD)
@@ -34,15 +44,13 @@ struct GroupedClipArgs {
   float R[kGroupsPerLaunch];
 };
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64)
 clip_factor_grouped_kernel(const float* __restrict__ sqnorm, int B, int mode, float stability,
                            float* __restrict__ C_out, float* __restrict__ norm_out,
                            const GroupedClipArgs ga) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  const int m = blockIdx.y;
-  if (i >= B) return;
-  float total = 0.f;
-  for (int l = ga.begin[m]; l < ga.begin[m + 1]; ++l) total += sqnorm[(size_t)l * B + i];
+  const int i = blockIdx.x, m = blockIdx.y;                  // one wave per (sample, group)
+  const float total = column_sum(sqnorm, B, i, ga.begin[m], ga.begin[m + 1]);
+  if (threadIdx.x != 0) return;
   const float norm = __builtin_sqrtf(fmaxf(total, 0.f));
   const float R = ga.R[m];
   const float c = mode == DP_CLIP_STANDARD ? fminf(R / norm, 1.f) : R / (norm + stability);
@@ -62,7 +70,7 @@ dp_status launch_clip_factors_grouped(const float* sqnorm, int B, const int32_t*
     ga.first_group = first;
     for (int m = 0; m <= ga.n_groups; ++m) ga.begin[m] = group_begin[first + m];
     for (int m = 0; m < ga.n_groups; ++m) ga.R[m] = R[first + m];
-    hipLaunchKernelGGL(clip_factor_grouped_kernel, dim3((B + 255) / 256, ga.n_groups), dim3(256), 0, s,
+    hipLaunchKernelGGL(clip_factor_grouped_kernel, dim3(B, ga.n_groups), dim3(64), 0, s,
                        sqnorm, B, mode, stability, C_out, norm_out, ga);
     if (hipGetLastError() != hipSuccess) return DP_ERR_HIP;
   }
@@ -71,7 +79,7 @@ dp_status launch_clip_factors_grouped(const float* sqnorm, int B, const int32_t*
 
 dp_status launch_clip_factors(const float* sqnorm, int L, int B, int mode, float R, float stability,
                               float* C_out, float* norm_out, hipStream_t s) {
-  hipLaunchKernelGGL(clip_factor_kernel, dim3((B + 255) / 256), dim3(256), 0, s, sqnorm, L, B, mode,
+  hipLaunchKernelGGL(clip_factor_kernel, dim3(B), dim3(64), 0, s, sqnorm, L, B, mode,
                      R, stability, C_out, norm_out);
   return hip_status(hipGetLastError());
 }
