@@ -12,6 +12,7 @@ timed loop) and the CPU oracle timed on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -70,6 +71,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg1", choices=sorted(si.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
+                    help="store a and g of a 16-bit workload in this type instead of the workload's own")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -81,6 +84,8 @@ def main():
     from paper_2311_11822_amd.pipeline import BkPipeline
 
     w = si.WORKLOADS[args.workload]
+    if args.dtype and w.dtype != si.F32:
+        w = dataclasses.replace(w, dtype={"bf16": si.BF16, "f16": si.F16}[args.dtype])
     baseline = None
     if not args.no_cpu_baseline:
         budget = {"cfg0": 1, "cfg1": 48, "cfg2": 16, "cfg3": 4, "cfg4": 1}[w.name]
@@ -124,7 +129,7 @@ def main():
     ms_norm, ms_clip, ms_grad, ms_noise = stage.mean(axis=0)
     ms_step = elapsed * 1e3 / args.steps
     norm_flops, grad_flops = workload_flops(w)
-    grad_launches = -(-w.L // 48) if w.dtype == si.BF16 else w.L
+    grad_launches = -(-w.L // 48) if w.dtype != si.F32 else w.L
     grad_tflops = grad_flops / (ms_grad * 1e-3) / 1e12
     # The gradient of one group of up to 48 layers is one launch of clipped_grad_big_kernel plus,
     # when the last round of tiles is nearly empty, one of clipped_grad_tail_kernel for those
@@ -146,7 +151,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == si.BF16 else "f32",
+        "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} T={w.T} L={w.L} layers, psi={w.psi}",
                    "clip": "automatic" if w.clip_mode == si.CLIP_AUTOMATIC else "standard",
@@ -155,7 +160,7 @@ def main():
         "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
         "noise_gbps": 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
-        "roofline": {"kernel": "clipped_grad_big_kernel (+ clipped_grad_tail_kernel)" if w.dtype == si.BF16
+        "roofline": {"kernel": "clipped_grad_big_kernel (+ clipped_grad_tail_kernel)" if w.dtype != si.F32
                      else "clipped_grad_f32_kernel",
                      "bound": "mfma",
                      "achieved": grad_tflops, "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",

@@ -46,7 +46,13 @@ typedef enum {
   DP_ERR_HIP = 4           /* the HIP runtime refused a launch */
 } dp_status;
 
-typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;             /* storage type of a and g */
+/* Storage type of a and g.  The 16-bit types are multiplied on the matrix cores and summed in
+ * fp32; every output is fp32.  DP_F16 is IEEE binary16 with subnormals honoured.  No loss scale
+ * is applied or expected anywhere (section 3.4, "Mixed-precision training with DP": the clip
+ * factor already does the scaling; and with fp32 sums the Gram entries and per-sample norms
+ * of the loss-scaling table cannot overflow).  For 16-bit types d_in and d_out must be multiples
+ * of 8. */
+typedef enum { DP_F32 = 0, DP_BF16 = 1, DP_F16 = 2 } dp_dtype;
 typedef enum { DP_CLIP_STANDARD = 0, DP_CLIP_AUTOMATIC = 1 } dp_clip_mode;
 typedef enum { DP_PATH_GHOST = 0, DP_PATH_PEREX = 1 } dp_path;
 

@@ -18,7 +18,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 DP_OK, DP_ERR_INVALID_ARG, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_HIP = range(5)
-DP_F32, DP_BF16 = 0, 1
+DP_F32, DP_BF16, DP_F16 = 0, 1, 2
 DP_CLIP_STANDARD, DP_CLIP_AUTOMATIC = 0, 1
 DP_PATH_GHOST, DP_PATH_PEREX = 0, 1
 

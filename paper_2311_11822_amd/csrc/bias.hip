@@ -13,10 +13,11 @@ constexpr int kRowGroups = 8, kColThreads = 32;
 
 // One workgroup: sample blockIdx.y, a strip of 32 * VEC columns.  Thread (rg, ct) adds rows
 // rg, rg + 8, ... of its VEC columns; the 8 row groups are then added in order through LDS.
-template <bool BF16>
+template <int DT>                       // dp_dtype of g
 __global__ void __launch_bounds__(kRowGroups* kColThreads)
 bias_colsum_kernel(const void* __restrict__ g_all, int T, int p, float* __restrict__ colsum) {
-  constexpr int VEC = BF16 ? 8 : 1;
+  constexpr bool HALF = DT != DP_F32;   // 16-bit storage: 8 columns per thread
+  constexpr int VEC = HALF ? 8 : 1;
   __shared__ float red[kRowGroups][kColThreads * VEC + 1];
   const int ct = threadIdx.x % kColThreads, rg = threadIdx.x / kColThreads;
   const int i = blockIdx.y;
@@ -25,15 +26,20 @@ bias_colsum_kernel(const void* __restrict__ g_all, int T, int p, float* __restri
 #pragma unroll
   for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
   if (col < p) {
-    if (BF16) {
+    if (HALF) {
       const uint16_t* g = static_cast<const uint16_t*>(g_all) + (size_t)i * T * p + col;
       for (int t = rg; t < T; t += kRowGroups) {
         const uint4 w = *reinterpret_cast<const uint4*>(g + (size_t)t * p);
         const uint32_t u[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          acc[2 * q] += __uint_as_float(u[q] << 16);             // bf16 -> fp32 is a shift
-          acc[2 * q + 1] += __uint_as_float(u[q] & 0xFFFF0000u);
+          if (DT == DP_BF16) {
+            acc[2 * q] += __uint_as_float(u[q] << 16);             // bf16 -> fp32 is a shift
+            acc[2 * q + 1] += __uint_as_float(u[q] & 0xFFFF0000u);
+          } else {
+            acc[2 * q] += (float)__builtin_bit_cast(_Float16, (uint16_t)(u[q] & 0xFFFFu));
+            acc[2 * q + 1] += (float)__builtin_bit_cast(_Float16, (uint16_t)(u[q] >> 16));
+          }
         }
       }
     } else {
@@ -84,14 +90,16 @@ clipped_bias_kernel(const float* __restrict__ colsum, int B, int p, const float*
 
 }  // namespace
 
-dp_status launch_bias_norm(const void* g, int is_bf16, int B, int T, int p, float* colsum,
+dp_status launch_bias_norm(const void* g, dp_dtype dt, int B, int T, int p, float* colsum,
                            float* sqnorm_out, hipStream_t s) {
-  const int cols_per_block = kColThreads * (is_bf16 ? 8 : 1);
+  const int cols_per_block = kColThreads * (dt == DP_F32 ? 1 : 8);
   const dim3 grid((p + cols_per_block - 1) / cols_per_block, B), block(kRowGroups * kColThreads);
-  if (is_bf16)
-    hipLaunchKernelGGL(bias_colsum_kernel<true>, grid, block, 0, s, g, T, p, colsum);
+  if (dt == DP_BF16)
+    hipLaunchKernelGGL(bias_colsum_kernel<DP_BF16>, grid, block, 0, s, g, T, p, colsum);
+  else if (dt == DP_F16)
+    hipLaunchKernelGGL(bias_colsum_kernel<DP_F16>, grid, block, 0, s, g, T, p, colsum);
   else
-    hipLaunchKernelGGL(bias_colsum_kernel<false>, grid, block, 0, s, g, T, p, colsum);
+    hipLaunchKernelGGL(bias_colsum_kernel<DP_F32>, grid, block, 0, s, g, T, p, colsum);
   if (hipGetLastError() != hipSuccess) return DP_ERR_HIP;
   hipLaunchKernelGGL(bias_sqnorm_kernel, dim3(B), dim3(256), 0, s, colsum, p, sqnorm_out);
   return hip_status(hipGetLastError());

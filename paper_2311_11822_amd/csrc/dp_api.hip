@@ -11,9 +11,11 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+bool dtype_ok(dp_dtype dt) { return dt == DP_F32 || dt == DP_BF16 || dt == DP_F16; }
+
 bool dims_ok(dp_dtype dt, int B, int T, int d, int p) {
   if (B <= 0 || T <= 0 || d <= 0 || p <= 0) return false;
-  if (dt == DP_BF16 && ((d & 7) || (p & 7))) return false;
+  if (dt != DP_F32 && ((d & 7) || (p & 7))) return false;      // 16-bit rows must be 16-byte multiples
   // index arithmetic inside the kernels is 64-bit for element offsets, 32-bit per dimension
   if ((int64_t)B * T > INT32_MAX) return false;
   return true;
@@ -41,12 +43,13 @@ int tiles_per_sample(int path, const dp_layer& ly) {
 enum NormKernel { kGhostBig, kGhostSmall, kPerex };
 
 dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, const std::vector<int>& which,
-                        const std::vector<int64_t>& part_begin, int B, float* partials,
+                        const std::vector<int64_t>& part_begin, dp_dtype dt, int B, float* partials,
                         float* sqnorm_out, hipStream_t s) {
   for (size_t begin = 0; begin < which.size(); begin += kMaxGroup) {
     GroupArgs ga;
     ga.B = B;
     ga.accumulate = 0;
+    ga.f16 = dt == DP_F16;
     ga.n_layers = (int)std::min<size_t>(kMaxGroup, which.size() - begin);
     int64_t blocks = 0;
     for (int j = 0; j < ga.n_layers; ++j) {
@@ -85,7 +88,7 @@ int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, std::vecto
     if (!dims_ok(dt, B, layers[l].T, layers[l].d_in, layers[l].d_out)) return -1;
     if (layers[l].path != DP_PATH_GHOST && layers[l].path != DP_PATH_PEREX) return -1;
     if (begin) begin->push_back(total);
-    if (dt == DP_BF16) total += (int64_t)tiles_per_sample(layers[l].path, layers[l]) * B;
+    if (dt != DP_F32) total += (int64_t)tiles_per_sample(layers[l].path, layers[l]) * B;
     if (total > INT32_MAX) return -1;
   }
   return total;
@@ -93,7 +96,7 @@ int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, std::vecto
 
 dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
                      size_t ws_bytes, hipStream_t s) {
-  if (dt != DP_F32 && dt != DP_BF16) return DP_ERR_INVALID_ARG;
+  if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!sqnorm_out) return DP_ERR_INVALID_ARG;
   std::vector<int64_t> begin;
   const int64_t slots = norm_slots(layers, L, dt, B, &begin);
@@ -124,11 +127,11 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
       (ghost_uses_big(layers[l]) ? ghost_big : ghost_small).push_back(l);
   }
   float* partials = static_cast<float*>(ws);
-  dp_status st = run_norm_path(kGhostBig, layers, ghost_big, begin, B, partials, sqnorm_out, s);
+  dp_status st = run_norm_path(kGhostBig, layers, ghost_big, begin, dt, B, partials, sqnorm_out, s);
   if (st != DP_OK) return st;
-  st = run_norm_path(kGhostSmall, layers, ghost_small, begin, B, partials, sqnorm_out, s);
+  st = run_norm_path(kGhostSmall, layers, ghost_small, begin, dt, B, partials, sqnorm_out, s);
   if (st != DP_OK) return st;
-  return run_norm_path(kPerex, layers, perex, begin, B, partials, sqnorm_out, s);
+  return run_norm_path(kPerex, layers, perex, begin, dt, B, partials, sqnorm_out, s);
 }
 
 dp_status single_norm(dp_path path, const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
@@ -173,7 +176,7 @@ size_t dp_norm_workspace_bytes(dp_path path, dp_dtype dt, int B, int T, int d_in
 }
 
 size_t dp_norms_multi_workspace_bytes(const dp_layer* layers, int L, dp_dtype dt, int B) {
-  if (dt != DP_F32 && dt != DP_BF16) return 0;
+  if (!dtype_ok(dt)) return 0;
   const int64_t slots = norm_slots(layers, L, dt, B, nullptr);
   if (slots < 0) return 0;
   // never 0 for a valid request, so "0 = invalid" stays unambiguous
@@ -213,7 +216,7 @@ namespace {
 // every layer uses C[i]).
 dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
                             const int* c_off, float* const* grads, int accumulate, void* stream) {
-  if (dt != DP_F32 && dt != DP_BF16) return DP_ERR_INVALID_ARG;
+  if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!layers || !grads || !C || L <= 0 || B <= 0) return DP_ERR_INVALID_ARG;
   if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
   for (int l = 0; l < L; ++l) {
@@ -249,6 +252,7 @@ dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, c
       GroupArgs ga;
       ga.B = B;
       ga.accumulate = accumulate;
+      ga.f16 = dt == DP_F16;
       ga.n_layers = 0;
       int64_t blocks = 0;
       while (pos < which.size() && ga.n_layers < kMaxGroup) {
@@ -325,11 +329,11 @@ float dp_group_noise_threshold(const float* R, int M) {
 
 dp_status dp_bias_norm(const void* g, dp_dtype dt, int B, int T, int d_out, float* colsum,
                        float* sqnorm_out, void* stream) {
-  if (dt != DP_F32 && dt != DP_BF16) return DP_ERR_INVALID_ARG;
+  if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!g || !colsum || !sqnorm_out || !aligned16(g)) return DP_ERR_INVALID_ARG;
   if (!dims_ok(dt, B, T, 8, d_out)) return DP_ERR_INVALID_ARG;
   if (B > 65535) return DP_ERR_UNSUPPORTED;
-  return launch_bias_norm(g, dt == DP_BF16, B, T, d_out, colsum, sqnorm_out, static_cast<hipStream_t>(stream));
+  return launch_bias_norm(g, dt, B, T, d_out, colsum, sqnorm_out, static_cast<hipStream_t>(stream));
 }
 
 dp_status dp_clipped_bias_grad(const float* colsum, int B, int d_out, const float* C, float* grad_b,

@@ -9,10 +9,23 @@
 namespace dpbk {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 #define DP_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+// One 32x32x16 matrix-core step on 16-bit operands with fp32 accumulation.  The kernels move
+// operands as opaque 16-bit values (typed bf16x8 for convenience); F16 says the bits are IEEE
+// binary16 rather than bfloat16, which only changes the instruction that multiplies them.
+template <bool F16>
+__device__ __forceinline__ f32x16 mfma16(bf16x8 a, bf16x8 b, f32x16 c) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b),
+                                                  c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
 
 // Up to this many layers travel in one launch's kernel arguments.
 constexpr int kMaxGroup = 48;
@@ -36,6 +49,7 @@ struct GroupArgs {
   int total_blocks;
   int B;
   int accumulate;
+  int f16;          // operands are IEEE binary16 (else bfloat16)
   GroupLayer layer[kMaxGroup];
 };
 
@@ -51,7 +65,7 @@ dp_status launch_clip_factors(const float* sqnorm, int L, int B, int mode, float
 dp_status launch_clip_factors_grouped(const float* sqnorm, int B, const int32_t* group_begin, int M,
                                       const float* R, int mode, float stability, float* C_out,
                                       float* norm_out, hipStream_t s);
-dp_status launch_bias_norm(const void* g, int is_bf16, int B, int T, int p, float* colsum,
+dp_status launch_bias_norm(const void* g, dp_dtype dt, int B, int T, int p, float* colsum,
                            float* sqnorm_out, hipStream_t s);
 dp_status launch_clipped_bias_grad(const float* colsum, int B, int p, const float* C, float* grad_b,
                                    int accumulate, hipStream_t s);

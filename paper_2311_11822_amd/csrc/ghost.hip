@@ -28,7 +28,7 @@ struct GramShape {
   static_assert(BK % 16 == 0 && (BT * BK / 8) % NT == 0, "tile shape");
 };
 
-template <class S>
+template <class S, bool F16>
 struct GramTile {
   const uint16_t* x;     // current operand of this sample: a_i or g_i, [T, width]
   int T, width;
@@ -82,7 +82,7 @@ struct GramTile {
       for (int i = 0; i < S::TM; ++i)
 #pragma unroll
         for (int j = 0; j < S::TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma16<F16>(fa[i], fb[j], acc[i][j]);
     }
   }
 
@@ -109,7 +109,7 @@ __device__ __forceinline__ int find_layer_g(const GroupArgs& ga, int block) {
   return l;
 }
 
-template <class S>
+template <class S, bool F16>
 __global__ void __launch_bounds__(S::NT)
 ghost_norm_kernel(const GroupArgs ga, float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -127,7 +127,7 @@ ghost_norm_kernel(const GroupArgs ga, float* __restrict__ partials) {
   }
   const int J = I + q;
 
-  GramTile<S> t;
+  GramTile<S, F16> t;
   t.T = ly.T;
   t.r0 = I * S::BT;
   t.c0 = J * S::BT;
@@ -181,8 +181,9 @@ int ghost_tiles_per_sample(int T) {
   return nt * (nt + 1) / 2;
 }
 
-dp_status launch_ghost_group(const GroupArgs& ga, float* partials, hipStream_t s) {
-  auto kernel = ghost_norm_kernel<GhostShape>;
+template <bool F16>
+dp_status launch_ghost_group_t(const GroupArgs& ga, float* partials, hipStream_t s) {
+  auto kernel = ghost_norm_kernel<GhostShape, F16>;
   dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                                 (int)GhostShape::LDS_BYTES));
@@ -190,6 +191,10 @@ dp_status launch_ghost_group(const GroupArgs& ga, float* partials, hipStream_t s
   hipLaunchKernelGGL(kernel, dim3(ga.total_blocks), dim3(GhostShape::NT), GhostShape::LDS_BYTES, s, ga,
                      partials);
   return hip_status(hipGetLastError());
+}
+
+dp_status launch_ghost_group(const GroupArgs& ga, float* partials, hipStream_t s) {
+  return ga.f16 ? launch_ghost_group_t<true>(ga, partials, s) : launch_ghost_group_t<false>(ga, partials, s);
 }
 
 }  // namespace dpbk

@@ -73,7 +73,7 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
 
 #define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
-template <bool COMPACT>
+template <bool COMPACT, bool F16>
 __global__ void __launch_bounds__(NT)
 ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   constexpr int STAGE_BYTES = Plan<COMPACT>::STAGE_BYTES, NSTAGE = Plan<COMPACT>::NSTAGE;
@@ -224,7 +224,7 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
           const int i = n >> 1, j = n & 1;
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma16<F16>(fa[cb][i], fb[cb][j], acc[i][j]);
           DP_PIN();
           if (ks < 3 && n < 6) read_frag(nb, n, c_stage, ks + 1);
           // 12 loads over 4 k-steps: after MFMA 3, 5 and 6 of each
@@ -270,7 +270,7 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
           const int i = n >> 1, j = n & 1;
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma16<F16>(fa[cb][i], fb[cb][j], acc[i][j]);
           DP_PIN();
           if (fetch && n < 6) read_frag(nb, n, r_stage, r_ks);
           if (n == 3) issue(ks * 2, false);            // 8 loads over 4 k-steps
@@ -326,10 +326,10 @@ bool ghost_big_supports(int T, int d, int p) {
          (int64_t)(T + TI) * p * 2 < (int64_t)1 << 31;
 }
 
-template <bool COMPACT>
+template <bool COMPACT, bool F16>
 dp_status launch_plan(const GroupArgs& ga, float* partials, hipStream_t s) {
   static bool ready = false;
-  auto kernel = ghost_big_kernel<COMPACT>;
+  auto kernel = ghost_big_kernel<COMPACT, F16>;
   if (!ready) {
     dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -344,7 +344,8 @@ dp_status launch_plan(const GroupArgs& ga, float* partials, hipStream_t s) {
 dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream_t s) {
   bool compact = true;
   for (int l = 0; l < ga.n_layers; ++l) compact = compact && ga.layer[l].T <= TI;
-  return compact ? launch_plan<true>(ga, partials, s) : launch_plan<false>(ga, partials, s);
+  if (ga.f16) return compact ? launch_plan<true, true>(ga, partials, s) : launch_plan<false, true>(ga, partials, s);
+  return compact ? launch_plan<true, false>(ga, partials, s) : launch_plan<false, false>(ga, partials, s);
 }
 
 }  // namespace dpbk

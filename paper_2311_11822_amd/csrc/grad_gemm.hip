@@ -110,6 +110,7 @@ __device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& lay
   n0 = (16 * sc + 8 * pc + rem / ph) * BN;
 }
 
+template <bool F16>
 __global__ void __launch_bounds__(NT)
 clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) {
   // The weights do not change during the kernel: read them through the constant address space
@@ -269,22 +270,22 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) 
         const int r_stage = ks == 0 ? c_stage : n_stage, r_ks = ks == 0 ? 1 : 0;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          acc[g][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][g].v, fb[cb][0].v, acc[g][0], 0, 0, 0);
+          acc[g][0] = mfma16<F16>(fa[cb][g].v, fb[cb][0].v, acc[g][0]);
           DP_PIN();
           if (fetch) read_frag(nb, 2 * g, r_stage, r_ks);
           DP_PIN();
-          acc[g][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][g].v, fb[cb][1].v, acc[g][1], 0, 0, 0);
+          acc[g][1] = mfma16<F16>(fa[cb][g].v, fb[cb][1].v, acc[g][1]);
           DP_PIN();
           if (fetch) read_frag(nb, 2 * g + 1, r_stage, r_ks);
           DP_PIN();
-          acc[g][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][g].v, fb[cb][2].v, acc[g][2], 0, 0, 0);
+          acc[g][2] = mfma16<F16>(fa[cb][g].v, fb[cb][2].v, acc[g][2]);
           DP_PIN();
           if (g & 1)
             prefetch_issue_b(ks * 2 + (g >> 1));
           else
             prefetch_issue_a(ks * 2 + (g >> 1));
           DP_PIN();
-          acc[g][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][g].v, fb[cb][3].v, acc[g][3], 0, 0, 0);
+          acc[g][3] = mfma16<F16>(fa[cb][g].v, fb[cb][3].v, acc[g][3]);
           DP_PIN();
         }
       }
@@ -402,7 +403,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 // conditional: the number of loads in flight is a compile-time constant and a thread waits only
 // for the slot it is about to store.  Two LDS stages, one barrier per k-block.  The k-steps of an output element are added in
 // the same order as in the large kernel.
-template <class S, int D>
+template <class S, int D, bool F16>
 __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int B, int accumulate,
                                                        int m0, int n0,
                                                        const __attribute__((address_space(4))) float* C,
@@ -448,7 +449,7 @@ __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fb[ks], c, 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) c = mfma16<F16>(fa[ks], fb[ks], c);
   };
   u32x4 sa[D][S::A_PER_T], sb[D][S::B_PER_T];
   f32x16 acc[S::TM][S::TN];
@@ -550,6 +551,7 @@ using TailShape = TnShape<DP_TAIL_SHAPE>;
 constexpr int TAIL = 64, SUBS_N = BN / TAIL, SUBS = (BM / TAIL) * SUBS_N;
 static_assert(TailShape::BM == TAIL && TailShape::BN == TAIL, "sub-tile shape");
 
+template <bool F16>
 __global__ void __launch_bounds__(TailShape::NT)
 clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, int first_tile) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_tail[];
@@ -566,7 +568,7 @@ clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, in
   if (m0 >= ly.d_in || n0 >= ly.d_out) return;       // sub-tile past the layer's edge (whole workgroup)
   const __attribute__((address_space(4))) float* C =
       (const __attribute__((address_space(4))) float*)(uintptr_t)(C_all + ly.c_off);
-  clipped_grad_tile_deep<TailShape, DP_TAIL_DEPTH>(ly, ga.B, ga.accumulate, m0, n0, C, lds_tail);
+  clipped_grad_tile_deep<TailShape, DP_TAIL_DEPTH, F16>(ly, ga.B, ga.accumulate, m0, n0, C, lds_tail);
 }
 
 }  // namespace
@@ -590,14 +592,16 @@ bool clipped_grad_big_supports(int T, int d, int p) {
 #endif
 constexpr int kRound = 256;           // compute units = large-tile workgroups resident at a time
 
-dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, hipStream_t s) {
+template <bool F16>
+dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, hipStream_t s) {
+  auto big = clipped_grad_big_kernel<F16>;
+  auto tail = clipped_grad_tail_kernel<F16>;
   static bool ready = false;
   if (!ready) {
-    dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(clipped_grad_big_kernel),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                  LDS_BYTES));
+    dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(big),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
     if (st != DP_OK) return st;
-    st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(clipped_grad_tail_kernel),
+    st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(tail),
                                         hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)TailShape::LDS_BYTES));
     if (st != DP_OK) return st;
@@ -609,14 +613,19 @@ dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, hip
   if (n > n_tail) {
     GroupArgs main_args = ga;
     main_args.total_blocks = n - n_tail;
-    hipLaunchKernelGGL(clipped_grad_big_kernel, dim3(n - n_tail), dim3(NT), LDS_BYTES, s, main_args, C);
+    hipLaunchKernelGGL(big, dim3(n - n_tail), dim3(NT), LDS_BYTES, s, main_args, C);
     dp_status st = hip_status(hipGetLastError());
     if (st != DP_OK) return st;
   }
   if (n_tail == 0) return DP_OK;
-  hipLaunchKernelGGL(clipped_grad_tail_kernel, dim3(n_tail * SUBS), dim3(TailShape::NT),
-                     TailShape::LDS_BYTES, s, ga, C, n - n_tail);
+  hipLaunchKernelGGL(tail, dim3(n_tail * SUBS), dim3(TailShape::NT), TailShape::LDS_BYTES, s, ga, C,
+                     n - n_tail);
   return hip_status(hipGetLastError());
+}
+
+dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, hipStream_t s) {
+  return ga.f16 ? launch_clipped_grad_big_group_t<true>(ga, C, s)
+                : launch_clipped_grad_big_group_t<false>(ga, C, s);
 }
 
 }  // namespace dpbk

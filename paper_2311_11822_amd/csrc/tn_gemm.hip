@@ -29,7 +29,7 @@ __device__ __forceinline__ int find_layer(const GroupArgs& ga, int block) {
 // ---------------------------------------------------------------------------------
 // Clip-weighted gradient, grouped over layers.
 // ---------------------------------------------------------------------------------
-template <class S>
+template <class S, bool F16>
 __global__ void __launch_bounds__(S::NT)
 clipped_grad_kernel(const GroupArgs ga, const float* __restrict__ C_all) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -38,14 +38,14 @@ clipped_grad_kernel(const GroupArgs ga, const float* __restrict__ C_all) {
   const int local = blockIdx.x - ly.tile_begin;
   const int tiles_n = (ly.d_out + S::BN - 1) / S::BN;
   const float* __restrict__ C = C_all + ly.c_off;      // the layer's clipping group
-  clipped_grad_tile<S>(ly, ga.B, ga.accumulate, (local / tiles_n) * S::BM, (local % tiles_n) * S::BN, C,
+  clipped_grad_tile<S, F16>(ly, ga.B, ga.accumulate, (local / tiles_n) * S::BM, (local % tiles_n) * S::BN, C,
                        lds);
 }
 
 // ---------------------------------------------------------------------------------
 // Instantiated per-sample norm, grouped over layers: one workgroup per (sample, tile).
 // ---------------------------------------------------------------------------------
-template <class S>
+template <class S, bool F16>
 __global__ void __launch_bounds__(S::NT)
 perex_norm_kernel(const GroupArgs ga, float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -74,7 +74,7 @@ perex_norm_kernel(const GroupArgs ga, float* __restrict__ partials) {
   for (int kb = 0, stage = 0; kb < nkb; ++kb, stage ^= 1) {
     const bool more = kb + 1 < nkb;
     if (more) t.gload(sample, kb + 1);
-    t.compute(lds + stage * S::STAGE, acc);
+    t.template compute<F16>(lds + stage * S::STAGE, acc);
     if (more) t.lds_store(lds + (stage ^ 1) * S::STAGE);
     __syncthreads();
   }
@@ -138,21 +138,31 @@ int clipped_grad_tiles(int d, int p) {
   return ((d + GradShape::BM - 1) / GradShape::BM) * ((p + GradShape::BN - 1) / GradShape::BN);
 }
 
-dp_status launch_clipped_grad_group(const GroupArgs& ga, const float* C, hipStream_t s) {
-  auto kernel = clipped_grad_kernel<GradShape>;
+template <bool F16>
+dp_status launch_clipped_grad_group_t(const GroupArgs& ga, const float* C, hipStream_t s) {
+  auto kernel = clipped_grad_kernel<GradShape, F16>;
   dp_status st = allow_lds(kernel, GradShape::LDS_BYTES);
   if (st != DP_OK) return st;
   hipLaunchKernelGGL(kernel, dim3(ga.total_blocks), dim3(GradShape::NT), GradShape::LDS_BYTES, s, ga, C);
   return hip_status(hipGetLastError());
 }
 
-dp_status launch_perex_group(const GroupArgs& ga, float* partials, hipStream_t s) {
-  auto kernel = perex_norm_kernel<PerexShape>;
+template <bool F16>
+dp_status launch_perex_group_t(const GroupArgs& ga, float* partials, hipStream_t s) {
+  auto kernel = perex_norm_kernel<PerexShape, F16>;
   dp_status st = allow_lds(kernel, PerexShape::LDS_BYTES);
   if (st != DP_OK) return st;
   hipLaunchKernelGGL(kernel, dim3(ga.total_blocks), dim3(PerexShape::NT), PerexShape::LDS_BYTES, s, ga,
                      partials);
   return hip_status(hipGetLastError());
+}
+
+dp_status launch_clipped_grad_group(const GroupArgs& ga, const float* C, hipStream_t s) {
+  return ga.f16 ? launch_clipped_grad_group_t<true>(ga, C, s) : launch_clipped_grad_group_t<false>(ga, C, s);
+}
+
+dp_status launch_perex_group(const GroupArgs& ga, float* partials, hipStream_t s) {
+  return ga.f16 ? launch_perex_group_t<true>(ga, partials, s) : launch_perex_group_t<false>(ga, partials, s);
 }
 
 dp_status launch_norm_reduce_group(const GroupArgs& ga, const float* partials, float* sqnorm_out,

@@ -89,6 +89,7 @@ struct TnTile {
     }
   }
 
+  template <bool F16>
   __device__ __forceinline__ void compute(const uint16_t* stage, f32x16 (&acc)[S::TM][S::TN]) const {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave / S::WN) * S::WTM, wn = (wave % S::WN) * S::WTN;
@@ -105,7 +106,7 @@ struct TnTile {
       for (int i = 0; i < S::TM; ++i)
 #pragma unroll
         for (int j = 0; j < S::TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma16<F16>(fa[i], fb[j], acc[i][j]);
     }
   }
 };
@@ -137,7 +138,7 @@ __device__ __forceinline__ void scale_acc(f32x16 (&acc)[S::TM][S::TN], float f) 
 // sum_{j<=i} (C_j / C_i) G_j while sample i is being added; crossing to the next sample
 // multiplies it by C_i / C_{i+1} and the epilogue by the last C.  Samples with C == 0 are
 // skipped.
-template <class S>
+template <class S, bool F16>
 __device__ __forceinline__ void clipped_grad_tile(const GroupLayer& ly, int B, int accumulate, int m0,
                                                   int n0, const float* __restrict__ C, uint16_t* lds) {
   TnTile<S> t;
@@ -171,7 +172,7 @@ __device__ __forceinline__ void clipped_grad_tile(const GroupLayer& ly, int B, i
       }
       const bool more = ni < B;
       if (more) t.gload(ni, nkb_next);
-      t.compute(lds + stage * S::STAGE, acc);
+      t.template compute<F16>(lds + stage * S::STAGE, acc);
       if (more) t.lds_store(lds + (stage ^ 1) * S::STAGE);
       __syncthreads();
       if (!more) break;

@@ -12,12 +12,13 @@ from . import binding as dp
 
 class BkPipeline:
     """layers: sequence of (a, g) device tensors, a [B,T,d_in], g [B,T,d_out]; bf16 tensors may be
-    given as torch.bfloat16 or as int16/uint16 bit patterns, fp32 as torch.float32."""
+    given as torch.bfloat16 or as int16/uint16 bit patterns, fp16 as torch.float16, fp32 as
+    torch.float32."""
 
     def __init__(self, layers: Sequence[Tuple[torch.Tensor, torch.Tensor]], paths: Optional[List[int]] = None):
         a0 = layers[0][0]
         self.device = a0.device
-        self.dt = dp.DP_F32 if a0.dtype == torch.float32 else dp.DP_BF16
+        self.dt = {torch.float32: dp.DP_F32, torch.float16: dp.DP_F16}.get(a0.dtype, dp.DP_BF16)
         self.B = a0.shape[0]
         self.layers = list(layers)
         self.dims = [(a.shape[1], a.shape[2], g.shape[2]) for a, g in layers]

@@ -21,6 +21,7 @@ import numpy as np
 
 F32 = "f32"
 BF16 = "bf16"
+F16 = "f16"
 
 CLIP_STANDARD = 0
 CLIP_AUTOMATIC = 1
@@ -29,7 +30,7 @@ CLIP_AUTOMATIC = 1
 @dataclass(frozen=True)
 class Workload:
     name: str
-    dtype: str                      # F32 or BF16 storage of a and g
+    dtype: str                      # F32, BF16 or F16 storage of a and g
     B: int                          # samples in the micro-batch
     T: int                          # tokens per sample
     layers: Tuple[Tuple[int, int], ...]   # (d_in, d_out) per linear layer
@@ -44,6 +45,7 @@ class Workload:
     noise_step: int = 0
     shard_count: int = 1            # noise goes to 1/shard_count of the flat gradient
     shard_rank: int = 0
+    a_std: float = 1.0              # standard deviation of activations
 
     @property
     def L(self) -> int:
@@ -111,20 +113,20 @@ def layer_g_scale(w: Workload, layer: int) -> float:
 def gen_tensor(w: Workload, layer: int, which: int, g_extra_scale: float = 1.0) -> np.ndarray:
     """One layer's activation (which=0, [B,T,d]) or output gradient (which=1, [B,T,p]).
 
-    Returns float32 for F32 workloads and uint16 bfloat16 bit patterns for BF16
-    workloads.  Every (layer, tensor, sample) has its own random stream, so the
+    Returns float32 for F32 workloads, uint16 bfloat16 bit patterns for BF16 workloads and
+    numpy float16 (IEEE binary16, rounded to nearest even, subnormals kept) for F16 workloads.  Every (layer, tensor, sample) has its own random stream, so the
     values do not depend on how many threads generate them.
     """
     d, p = w.layers[layer]
     width = d if which == 0 else p
-    std = 1.0 if which == 0 else w.g_std * layer_g_scale(w, layer) * g_extra_scale
-    out = np.empty((w.B, w.T, width), dtype=np.float32 if w.dtype == F32 else np.uint16)
+    std = w.a_std if which == 0 else w.g_std * layer_g_scale(w, layer) * g_extra_scale
+    out = np.empty((w.B, w.T, width), dtype={F32: np.float32, BF16: np.uint16, F16: np.float16}[w.dtype])
 
     def one(i: int) -> None:
         x = _rng(w.data_seed, layer, which, i).standard_normal((w.T, width), dtype=np.float32)
         if std != 1.0:
             x *= np.float32(std)
-        out[i] = x if w.dtype == F32 else f32_to_bf16_bits(x)
+        out[i] = f32_to_bf16_bits(x) if w.dtype == BF16 else x      # assignment rounds to float16 for F16
 
     if w.B * w.T * width < (1 << 20):
         for i in range(w.B):
@@ -140,7 +142,7 @@ def gen_layer(w: Workload, layer: int, g_extra_scale: float = 1.0):
 
 
 def to_f64(x: np.ndarray) -> np.ndarray:
-    """Exact widening of stored inputs (float32, or bfloat16 bits) to float64."""
+    """Exact widening of stored inputs (float32, float16, or bfloat16 bits) to float64."""
     if x.dtype == np.uint16:
         return bf16_bits_to_f32(x).astype(np.float64)
     return x.astype(np.float64)
@@ -148,7 +150,7 @@ def to_f64(x: np.ndarray) -> np.ndarray:
 
 def small_workload(name: str, dtype: str, B: int, T: int, layers, **kw) -> Workload:
     """Ad-hoc workload for parity tests on ragged shapes."""
-    base = dict(g_std=1e-2 if dtype == BF16 else 1.0, g_layer_scale=False,
+    base = dict(g_std=1.0 if dtype == F32 else 1e-2, g_layer_scale=False,
                 clip_mode=CLIP_STANDARD, R=1.0, sigma=1.0)
     base.update(kw)
     return Workload(name, dtype, B, T, tuple(tuple(x) for x in layers), **base)

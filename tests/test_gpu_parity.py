@@ -40,6 +40,13 @@ def dev(x: np.ndarray):
     return torch.from_numpy(x).cuda()
 
 
+def dt_of(dp, dtype):
+    return {si.F32: dp.DP_F32, si.BF16: dp.DP_BF16, si.F16: dp.DP_F16}[dtype]
+
+
+HALF_TYPES = [si.BF16, si.F16]
+
+
 def host(t) -> np.ndarray:
     torch.cuda.synchronize()
     return t.detach().cpu().numpy()
@@ -211,29 +218,33 @@ BF16_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("dtype", HALF_TYPES)
 @pytest.mark.parametrize("B,T,d,p", BF16_SHAPES)
-def test_bf16_norms(dp, B, T, d, p):
-    w = si.small_workload("b", si.BF16, B, T, [(d, p)])
+def test_bf16_norms(dp, B, T, d, p, dtype):
+    w = si.small_workload("b", dtype, B, T, [(d, p)])
+    DT = dt_of(dp, dtype)
     a, g = si.gen_layer(w, 0)
     a64, g64 = si.to_f64(a), si.to_f64(g)
     want = o.perex_sqnorm(a64, g64)
     np.testing.assert_allclose(o.ghost_sqnorm(a64, g64), want, rtol=1e-9)
     ad, gd = dev(a), dev(g)
     for path, fn in ((dp.DP_PATH_GHOST, dp.dp_ghost_norm), (dp.DP_PATH_PEREX, dp.dp_perex_norm)):
-        nbytes = dp.dp_norm_workspace_bytes(path, dp.DP_BF16, B, T, d, p)
+        nbytes = dp.dp_norm_workspace_bytes(path, DT, B, T, d, p)
         assert nbytes > 0
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         out = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
-        fn(ad, gd, dp.DP_BF16, B, T, d, p, out, ws)
+        fn(ad, gd, DT, B, T, d, p, out, ws)
         assert rel(host(out), want) <= TOL_BF16_NORM, (path, host(out), want)
         first = host(out).copy()
-        fn(ad, gd, dp.DP_BF16, B, T, d, p, out, ws)
+        fn(ad, gd, DT, B, T, d, p, out, ws)
         np.testing.assert_array_equal(host(out), first)       # deterministic
 
 
+@pytest.mark.parametrize("dtype", HALF_TYPES)
 @pytest.mark.parametrize("B,T,d,p", BF16_SHAPES)
-def test_bf16_clipped_grad(dp, B, T, d, p):
-    w = si.small_workload("b", si.BF16, B, T, [(d, p)])
+def test_bf16_clipped_grad(dp, B, T, d, p, dtype):
+    w = si.small_workload("b", dtype, B, T, [(d, p)])
+    DT = dt_of(dp, dtype)
     a, g = si.gen_layer(w, 0)
     a64, g64 = si.to_f64(a), si.to_f64(g)
     C = np.random.default_rng(2).uniform(1e-3, 1.0, B).astype(np.float32)
@@ -242,18 +253,18 @@ def test_bf16_clipped_grad(dp, B, T, d, p):
         C[2] = 1.0
     ad, gd, Cd = dev(a), dev(g), dev(C)
     grad = torch.full((d, p), 3.0, dtype=torch.float32, device="cuda")
-    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Cd, grad, 0)
+    dp.dp_clipped_grad(ad, gd, DT, B, T, d, p, Cd, grad, 0)
     G = o.clipped_grad(a64, g64, C.astype(np.float64))
     assert frob(host(grad), G) <= TOL_BF16_GRAD
     assert frob(host(grad), G) <= 1e-5          # products are exact: only fp32 summation differs
-    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Cd, grad, 1)
+    dp.dp_clipped_grad(ad, gd, DT, B, T, d, p, Cd, grad, 1)
     assert frob(host(grad), 2 * G) <= 1e-5
     # all factors zero: the gradient is zero (overwrite) and unchanged (accumulate)
     Z = torch.zeros(B, dtype=torch.float32, device="cuda")
     before = host(grad).copy()
-    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Z, grad, 1)
+    dp.dp_clipped_grad(ad, gd, DT, B, T, d, p, Z, grad, 1)
     np.testing.assert_array_equal(host(grad), before)
-    dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Z, grad, 0)
+    dp.dp_clipped_grad(ad, gd, DT, B, T, d, p, Z, grad, 0)
     assert not host(grad).any()
 
 
@@ -269,10 +280,11 @@ def test_bf16_unclipped_is_plain_product(dp):
     assert frob(host(grad), want) <= 1e-5
 
 
-def test_multi_layer_stack_mixed_paths(dp, Pipe):
+@pytest.mark.parametrize("dtype", HALF_TYPES)
+def test_multi_layer_stack_mixed_paths(dp, Pipe, dtype):
     # A stack whose layers take different norm paths and shapes, in one grouped launch each.
     dims = [(72, 264), (264, 72), (8, 8), (136, 136), (520, 16)]
-    w = si.small_workload("m", si.BF16, 3, 150, dims, clip_mode=si.CLIP_AUTOMATIC)
+    w = si.small_workload("m", dtype, 3, 150, dims, clip_mode=si.CLIP_AUTOMATIC)
     layers = gen(w)
     l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
     paths = [0, 1, 1, 0, 1]
@@ -399,12 +411,13 @@ def test_grouped_clip_factors(dp, mode):
 
 
 @pytest.mark.parametrize("dtype,B,T,p", [(si.F32, 3, 5, 7), (si.BF16, 2, 300, 520), (si.BF16, 8, 512, 5120),
-                                         (si.BF16, 1, 1, 8), (si.F32, 4, 8, 16)])
+                                         (si.BF16, 1, 1, 8), (si.F32, 4, 8, 16), (si.F16, 2, 300, 520),
+                                         (si.F16, 3, 64, 8)])
 def test_bias_norm_and_clipped_bias_grad(dp, dtype, B, T, p):
     w = si.small_workload("bias", dtype, B, T, [(8, p)])
     g = si.gen_tensor(w, 0, 1)
     g64 = si.to_f64(g)
-    dt = dp.DP_F32 if dtype == si.F32 else dp.DP_BF16
+    dt = dt_of(dp, dtype)
     colsum = torch.full((B, p), -1.0, dtype=torch.float32, device="cuda")
     sq = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
     dp.dp_bias_norm(dev(g), dt, B, T, p, colsum, sq)
@@ -421,16 +434,16 @@ def test_bias_norm_and_clipped_bias_grad(dp, dtype, B, T, p):
     assert frob(host(gb), 2 * want) <= 1e-5 or np.linalg.norm(want) == 0
 
 
-@pytest.mark.parametrize("dtype", [si.F32, si.BF16])
+@pytest.mark.parametrize("dtype", [si.F32, si.BF16, si.F16])
 def test_layerwise_clipping_with_biases(dp, dtype):
     # The paper's default setting: one clipping group per layer (weight + bias), noise level
     # sigma * ||R||_2; flattened result [W_0, b_0, W_1, b_1, ...].
-    dims = [(72, 264), (264, 136), (136, 16)] if dtype == si.BF16 else [(4, 8), (8, 4), (4, 12)]
-    B, T = (3, 150) if dtype == si.BF16 else (4, 6)
-    w = si.small_workload("lw", dtype, B, T, dims, g_std=1e-2 if dtype == si.BF16 else 1.0)
+    dims = [(72, 264), (264, 136), (136, 16)] if dtype != si.F32 else [(4, 8), (8, 4), (4, 12)]
+    B, T = (3, 150) if dtype != si.F32 else (4, 6)
+    w = si.small_workload("lw", dtype, B, T, dims, g_std=1e-2 if dtype != si.F32 else 1.0)
     layers = gen(w)
     l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
-    dt = dp.DP_F32 if dtype == si.F32 else dp.DP_BF16
+    dt = dt_of(dp, dtype)
     L, M = len(dims), len(dims)
     R = [0.05, 0.2, 1e3]
     sigma = 0.3
@@ -482,6 +495,61 @@ def test_layerwise_clipping_with_biases(dp, dtype):
 # error paths: every refusal happens on the host, nothing is launched
 # ----------------------------------------------------------------------------
 
+# ----------------------------------------------------------------------------
+# fp16 inputs without loss scaling (section 3.4 and the loss-scaling table)
+# ----------------------------------------------------------------------------
+
+def fp16_path_check(dp, Pipe, w, tol_norm=TOL_BF16_NORM):
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    assert pipe.dt == dp.DP_F16
+    pipe.norms()
+    pipe.clip(w.clip_mode, w.R, w.stability)
+    pipe.grad()
+    sqn = np.stack([(o.ghost_sqnorm if path == o.PATH_GHOST else o.perex_sqnorm)(a, g)
+                    for (a, g), path in zip(l64, pipe.paths)])
+    assert np.all(np.isfinite(host(pipe.sqnorm)))
+    assert rel(host(pipe.sqnorm), sqn) <= tol_norm
+    C, _ = o.clip_factors(sqn, w.clip_mode, w.R, w.stability)
+    assert rel(host(pipe.C), C) <= tol_norm
+    for l, (a, g) in enumerate(l64):
+        assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, C)) <= 1e-4
+    return pipe, l64, sqn
+
+
+def test_fp16_gpt_block_stack(dp, Pipe):
+    # one GPT-shaped block (d = 256) at T = 256: large-tile gradient kernel, compact ghost plan,
+    # and the instantiated norm on the square layer
+    w = si.small_workload("h", si.F16, 4, 256, [(256, 768), (256, 256), (256, 1024), (1024, 256)],
+                          clip_mode=si.CLIP_AUTOMATIC)
+    pipe, _, _ = fp16_path_check(dp, Pipe, w)
+    assert pipe.paths == [o.choose_path(w.T, d, p) for d, p in w.layers] == [0, 1, 0, 0]
+
+
+def test_fp16_underflow_range_is_honoured(dp, Pipe):
+    # Output gradients of 1e-6 are subnormal in fp16 (below 6.1e-5; spacing 6e-8), the low end of
+    # the range the loss-scaling table lists for training without a loss scale.  They must reach
+    # the sums as they are stored, not as zeros.
+    w = si.small_workload("u", si.F16, 3, 160, [(136, 264), (264, 72)], g_std=1e-6,
+                          clip_mode=si.CLIP_AUTOMATIC)
+    g = si.gen_tensor(w, 0, 1)
+    assert np.all(np.abs(g.astype(np.float64)) < 6.2e-5) and (g != 0).mean() > 0.9     # all subnormal
+    pipe, _, sqn = fp16_path_check(dp, Pipe, w)
+    assert np.all(sqn > 0) and np.all(host(pipe.sqnorm) > 0)
+
+
+def test_fp16_large_range_does_not_overflow(dp, Pipe):
+    # Activations of order 1e2 and a loss-scaled output gradient of order 10: Gram entries reach
+    # 1e6 and above, beyond fp16's largest number (65504), the overflow the loss-scaling table
+    # marks.  They are formed and summed in fp32 here, so the norms stay finite and correct.
+    w = si.small_workload("o", si.F16, 2, 300, [(136, 264), (264, 136)], g_std=10.0, a_std=100.0)
+    a = si.to_f64(si.gen_tensor(w, 0, 0))
+    assert np.max(a[0] @ a[0].T) > 65504.0
+    pipe, _, sqn = fp16_path_check(dp, Pipe, w)
+    assert np.all(host(pipe.C) < 1e-6)                 # clipping does the scaling down
+
+
 def test_argument_errors(dp):
     x = torch.zeros(4096, dtype=torch.float32, device="cuda")
     lib = dp.lib
@@ -491,6 +559,7 @@ def test_argument_errors(dp):
     assert lib.dp_ghost_norm(p, p, 1, 1, 8, 12, 8, p, p, 64, None) == INV      # bf16 row not 16 B
     assert lib.dp_ghost_norm(p, p, 1, 0, 8, 8, 8, p, p, 64, None) == INV
     assert lib.dp_ghost_norm(p, p, 7, 1, 8, 8, 8, p, p, 64, None) == INV       # bad dtype
+    assert lib.dp_ghost_norm(p, p, 2, 1, 8, 12, 8, p, p, 64, None) == INV      # fp16 row not 16 B
     assert lib.dp_ghost_norm(p + 2, p, 1, 1, 8, 8, 8, p, p, 64, None) == INV   # misaligned
     assert lib.dp_ghost_norm(p, p, 1, 1, 8, 8, 8, p, None, 0, None) == WSP
     assert lib.dp_perex_norm(p, p, 1, 1, 8, 8, 8, p, p, 2, None) == WSP
