@@ -215,6 +215,11 @@ BF16_SHAPES = [
     (1, 257, 8, 8),          # minimum widths
     (5, 64, 392, 24),
     (2, 513, 256, 256),      # exact tile multiples plus one token
+    # T a multiple of 32 and widths >= 128: the large-tile gradient kernels
+    (3, 160, 136, 264),      # 2 tiles, all computed as 64 x 64 sub-tiles; edges inside sub-tiles
+    (2, 96, 392, 520),       # 6 tiles (sub-tile kernel), sub-tiles wholly past the edge
+    (2, 64, 1800, 1544),     # 56 tiles: one short round of 256 x 256 tiles, ragged edges
+    (2, 32, 4360, 3848),     # 288 tiles: a full round of large tiles plus 32 tiles of sub-tiles
 ]
 
 
