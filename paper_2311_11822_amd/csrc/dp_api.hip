@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument validation, grouping of layers into launches.
 // No device code lives here and no device memory is allocated.
 #include <math.h>
+#include <algorithm>
 #include <vector>
 
 #include "dp_internal.h"
@@ -42,9 +43,18 @@ int tiles_per_sample(int path, const dp_layer& ly) {
 // part_begin[l] is the layer's first slot in the partial-sum workspace.
 enum NormKernel { kGhostBig, kGhostSmall, kPerex };
 
-dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, const std::vector<int>& which,
+dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, std::vector<int> which,
                         const std::vector<int64_t>& part_begin, dp_dtype dt, int B, float* partials,
                         float* sqnorm_out, hipStream_t s) {
+  // A tile's length is the contraction it runs over (d_in + d_out for the ghost norm, T for the
+  // instantiated one).  Longest first: workgroups are handed out in order, so the short tiles
+  // fill the end of the launch.  Each layer writes its own workspace slots and sqnorm row, so
+  // the order inside a launch is free.
+  std::stable_sort(which.begin(), which.end(), [&](int x, int y) {
+    const int64_t lx = kernel == kPerex ? layers[x].T : (int64_t)layers[x].d_in + layers[x].d_out;
+    const int64_t ly = kernel == kPerex ? layers[y].T : (int64_t)layers[y].d_in + layers[y].d_out;
+    return lx > ly;
+  });
   for (size_t begin = 0; begin < which.size(); begin += kMaxGroup) {
     GroupArgs ga;
     ga.B = B;

@@ -6,8 +6,10 @@
 // d_in, then the tile of g g^T over d_out, in two accumulator sets (4 waves x 128 x 64 x 2 sets
 // = all 256 accumulator registers per lane), multiplies them element by element and reduces to
 // one partial sum.  Both Gram matrices are symmetric, so 128 x 128 sub-blocks above the
-// diagonal count twice, diagonal ones once and the one sub-block per tile row that lies below
-// the diagonal is skipped.  No T x T matrix is written to memory.
+// diagonal count twice and diagonal ones once.  The first tile of a tile row (J = 2I) holds one
+// diagonal sub-block and one below the diagonal, which is not needed: that tile runs in
+// "diagonal mode", the four waves sharing its one 128 x 128 sub-block (64 x 64 each), with half
+// the loads and half the MFMAs of a full tile.  No T x T matrix is written to memory.
 //
 // Data path (same machinery as the gradient kernel in grad_gemm.hip): operand rows go from
 // global memory to LDS without passing through registers (buffer_load ... lds), three stages
@@ -73,6 +75,13 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
 
 #define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
+// After which MFMA of a k-step (2 MI MFMAs) load x of its per_ks global->LDS loads is issued.
+constexpr int load_slot(int mi, int per_ks, int x) {
+  if (mi == 2) return 2;                                       // 4 MFMAs, one load
+  if (per_ks == 3) return x == 0 ? 3 : (x == 1 ? 5 : 6);       // 8 MFMAs, three loads
+  return x == 0 ? 3 : 6;                                       // 8 MFMAs, two loads
+}
+
 template <bool COMPACT, bool F16>
 __global__ void __launch_bounds__(NT)
 ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
@@ -80,14 +89,25 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   const unsigned lds0 = (unsigned)(uintptr_t)lds_raw;
 
-  // XCD-aware order.  Workgroup b runs on XCD b % 8 (round-robin dispatch); the tiles of one
-  // sample read the same token rows, so each XCD takes one contiguous range of tile numbers
-  // and a sample's tiles meet in one L2 instead of being fetched by up to eight.
+  // XCD-aware order.  Workgroup b runs on XCD b % 8 (round-robin dispatch), and the tiles of one
+  // sample read the same token rows: each XCD takes chunks of 32 consecutive tile numbers, so
+  // that a sample's tiles meet in one L2 instead of being fetched by up to eight.  Tiles of
+  // different layers differ in length (d_in + d_out), so the chunks are dealt out cyclically
+  // and the deal rotates by one XCD per round of 256 tiles: every XCD then sees every part of
+  // the launch, whatever the period of the layer pattern (contiguous eighths of the launch
+  // leave the XCDs with unequal work).
   int logical;
   {
-    const int n = ga.total_blocks, per = n >> 3, rest = n & 7;
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    logical = xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx;
+    constexpr int CHUNK = 32, ROUND = 8 * CHUNK;
+    const int n = ga.total_blocks;
+    const int round = blockIdx.x / ROUND, base = round * ROUND, qd = blockIdx.x - base;
+    const int xcd = qd & 7, idx = qd >> 3;
+    if (base + ROUND <= n) {
+      logical = base + ((xcd - round) & 7) * CHUNK + idx;
+    } else {                                      // last, partial round: contiguous eighths
+      const int m = n - base, per = m >> 3, rest = m & 7;
+      logical = base + (xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx);
+    }
   }
   int l = 0;
   while (l + 1 < ga.n_layers && logical >= ga.layer[l + 1].tile_begin) ++l;
@@ -107,12 +127,16 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   const int r0 = I * TI, c0 = J * TJ;
   const bool inside = q < 2;                      // column block is one half of the row block
 
+  const bool diag = q == 0;                       // only the sub-block (2I, 2I) is needed
+
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 64;
-  // weight of this wave's 128 x 128 sub-block (rows r0 + wm): above / on / below the diagonal
-  const int sub_row = 2 * I + (wave >> 1);
-  const float weight = J > sub_row ? 2.f : (J == sub_row ? 1.f : 0.f);
+  // full tile: waves 2 x 2 of 128 x 64; diagonal mode: 2 x 2 of 64 x 64 on rows [r0, r0 + 128)
+  const int wm = (wave >> 1) * (diag ? 64 : 128), wn = (wave & 1) * 64;
+  // weight of this wave's sub-block: above the diagonal twice, on it once (a full tile has
+  // J >= 2I + 1, so none of its two sub-block rows 2I, 2I + 1 lies below the diagonal)
+  const float weight = (!diag && J > 2 * I + (wave >> 1)) ? 2.f : 1.f;
+  const int li = diag ? LOADS_I / 2 : LOADS_I;    // wave-loads of the row block per wave and k-block
 
   // ---- prefetch stream ---------------------------------------------------------------
   // Wave-load j of the row block covers rows (wave*8 + j)*8 + (lane >> 3); the lane's LDS chunk
@@ -126,7 +150,7 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
     rs = make_rsrc(static_cast<const unsigned char*>(base) + (size_t)sample * slab, slab);
 #pragma unroll
     for (int j = 0; j < LOADS_I; ++j) {
-      const int row = (wave * LOADS_I + j) * 8 + (lane >> 3);
+      const int row = (wave * li + j) * 8 + (lane >> 3);
       const int chunk = (lane & 7) ^ ((row >> 1) & 7);
       vi[j] = (unsigned)(r0 + row) * width * 2u + chunk * 16u;     // rows >= T: past the slab -> zeros
     }
@@ -139,14 +163,15 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   };
   int p_blk = 0, p_stage = 0;
   unsigned p_soff = 0;
+  // this wave's first LDS destination inside a stage, row block and column block
+  const unsigned ld_i = lds0 + wave * li * 1024, ld_j = lds0 + I_BYTES + wave * LOADS_J * 1024;
   set_operand(ly.a, ly.d_in);
   // item in 0 .. LOADS_I + LOADS_J - 1: one wave-load of the row block or of the column block
   auto issue = [&](int item, bool with_j) {
-    const unsigned st = lds0 + p_stage * STAGE_BYTES;
     if (item < LOADS_I)
-      load_to_lds(rs, vi[item], p_soff, st + (wave * LOADS_I + item) * 1024);
+      load_to_lds(rs, vi[item], p_soff, ld_i + p_stage * STAGE_BYTES + item * 1024);
     else if (with_j)
-      load_to_lds(rs, vj[item - LOADS_I], p_soff, st + I_BYTES + (wave * LOADS_J + item - LOADS_I) * 1024);
+      load_to_lds(rs, vj[item - LOADS_I], p_soff, ld_j + p_stage * STAGE_BYTES + (item - LOADS_I) * 1024);
   };
   auto advance = [&]() {
     ++p_blk;
@@ -187,7 +212,7 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
       }
 
   bf16x8 fa[2][4], fb[2][2];
-  // item 0,1: column-block fragments; 2..5: row-block fragments (needed in that order)
+  // item 0,1: column-block fragments; 2..: row-block fragments (needed in that order)
   auto read_frag = [&](int buf, int item, int stage, int ks) {
     const unsigned o = rd[ks] + stage * STAGE_BYTES;
     if (item < 2)
@@ -196,19 +221,32 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
       fa[buf][item - 2] = lds_read16(o + a_org + (item - 2) * 32 * ROW_BYTES);
   };
 
-  // Loads per k-block differ (12, or 8 when the column block is inside the row block); the
-  // vmcnt immediates must be constants, hence separate instantiations of the loop.
+  // Loads per k-block differ (12 for a full tile, 8 when its column block is inside the row
+  // block, 4 in diagonal mode) and so do the MFMAs per k-step (2 MI, with MI = 4 or 2 row tiles
+  // per wave); the vmcnt immediates and the interleave must be constants, hence separate
+  // instantiations of the loop.
   //
   // General plan, iteration kb: a wave waits for its own loads of block kb, meets the others at
   // one barrier (block kb is in LDS, block kb-1 is no longer read), fetches the first fragments,
-  // then runs 32 MFMAs with the loads of block kb+2 (into the stage of block kb-1) and the
+  // then runs the MFMAs with the loads of block kb+2 (into the stage of block kb-1) and the
   // fragment reads of the next k-step in their shadow.  A load has two iterations to land.
-  auto run = [&](auto inside_tag) {
+  auto run = [&](auto inside_tag, auto mi_tag) {
     constexpr bool ins = decltype(inside_tag)::value;
-    constexpr int PER = ins ? LOADS_I : LOADS_I + LOADS_J;
+    constexpr int MI = decltype(mi_tag)::value;
+    constexpr int LI = 2 * MI;                                  // row-block wave-loads per k-block
+    constexpr int PER = ins ? LI : LI + LOADS_J;
+    constexpr int PER_KS = PER / 4;                             // loads issued per k-step
+    static_assert(ins || MI == 4, "diagonal mode never loads a column block");
+    // load number x (0 .. PER-1) of a k-block
+    auto issue_nth = [&](int x) {
+      if (x < LI)
+        issue(x, false);
+      else
+        issue(LOADS_I + x - LI, true);
+    };
     for (int s = 0; s < NSTAGE - 1; ++s) {
 #pragma unroll
-      for (int it = 0; it < LOADS_I + LOADS_J; ++it) issue(it, !ins);
+      for (int x = 0; x < PER; ++x) issue_nth(x);
       advance();
     }
     int c_stage = 0;
@@ -216,21 +254,20 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * PER) : "memory");
       __builtin_amdgcn_s_barrier();
 #pragma unroll
-      for (int it = 0; it < 6; ++it) read_frag(0, it, c_stage, 0);
+      for (int it = 0; it < 2 + MI; ++it) read_frag(0, it, c_stage, 0);
       DP_PIN();
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const int cb = ks & 1, nb = cb ^ 1;
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {
+        for (int n = 0; n < 2 * MI; ++n) {
           const int i = n >> 1, j = n & 1;
           acc[i][j] = mfma16<F16>(fa[cb][i], fb[cb][j], acc[i][j]);
           DP_PIN();
-          if (ks < 3 && n < 6) read_frag(nb, n, c_stage, ks + 1);
-          // 12 loads over 4 k-steps: after MFMA 3, 5 and 6 of each
-          if (n == 3) issue(ks * 3, !ins);
-          if (n == 5) issue(ks * 3 + 1, !ins);
-          if (n == 6) issue(ks * 3 + 2, !ins);
+          if (ks < 3 && n < 2 + MI) read_frag(nb, n, c_stage, ks + 1);
+#pragma unroll
+          for (int x = 0; x < PER_KS; ++x)
+            if (n == load_slot(MI, PER_KS, x)) issue_nth(ks * PER_KS + x);
           DP_PIN();
         }
       }
@@ -242,19 +279,20 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
   // Compact plan, iteration kb: wait for own loads of block kb+1, barrier (block kb+1 in LDS,
-  // block kb-1 no longer read), issue block kb+4, 32 MFMAs; the fragments of the next k-step,
+  // block kb-1 no longer read), issue block kb+4, the MFMAs; the fragments of the next k-step,
   // including the first one of block kb+1, are read during the MFMAs.  Three iterations per load.
-  auto run_compact = [&]() {
-    constexpr int PER = LOADS_I;
+  auto run_compact = [&](auto mi_tag) {
+    constexpr int MI = decltype(mi_tag)::value;
+    constexpr int PER = 2 * MI, PER_KS = PER / 4;
     for (int s = 0; s < NSTAGE - 1; ++s) {
 #pragma unroll
-      for (int it = 0; it < LOADS_I; ++it) issue(it, false);
+      for (int it = 0; it < PER; ++it) issue(it, false);
       advance();
     }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * PER) : "memory");
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < 6; ++it) read_frag(0, it, 0, 0);
+    for (int it = 0; it < 2 + MI; ++it) read_frag(0, it, 0, 0);
     int c_stage = 0;
     auto block = [&](f32x16 (&acc)[4][2], auto last_tag) {
       constexpr bool last = decltype(last_tag)::value;
@@ -268,13 +306,14 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
         const bool fetch = ks < 3 || !last;
         const int r_stage = ks < 3 ? c_stage : n_stage, r_ks = ks < 3 ? ks + 1 : 0;
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {
+        for (int n = 0; n < 2 * MI; ++n) {
           const int i = n >> 1, j = n & 1;
           acc[i][j] = mfma16<F16>(fa[cb][i], fb[cb][j], acc[i][j]);
           DP_PIN();
-          if (fetch && n < 6) read_frag(nb, n, r_stage, r_ks);
-          if (n == 3) issue(ks * 2, false);            // 8 loads over 4 k-steps
-          if (n == 6) issue(ks * 2 + 1, false);
+          if (fetch && n < 2 + MI) read_frag(nb, n, r_stage, r_ks);
+#pragma unroll
+          for (int x = 0; x < PER_KS; ++x)
+            if (n == load_slot(MI, PER_KS, x)) issue(ks * PER_KS + x, false);
           DP_PIN();
         }
       }
@@ -286,12 +325,20 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
     block(sg, std::true_type{});
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
-  if (COMPACT)
-    run_compact();
-  else if (inside)
-    run(std::true_type{});
-  else
-    run(std::false_type{});
+  using Full = std::integral_constant<int, 4>;
+  using Half = std::integral_constant<int, 2>;
+  if (COMPACT) {
+    if (diag)
+      run_compact(Half{});
+    else
+      run_compact(Full{});
+  } else if (diag) {
+    run(std::true_type{}, Half{});
+  } else if (inside) {
+    run(std::true_type{}, Full{});
+  } else {
+    run(std::false_type{}, Full{});
+  }
 
   // Token rows/columns past T were fetched as zeros: their Gram entries are zero.
   float s = 0.f;
