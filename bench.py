@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg1", choices=sorted(si.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-noise", action="store_true",
+                    help="add the noise in the gradient kernels' epilogue (dp_clipped_grad_noise_multi) "
+                         "instead of in a pass of its own (dp_add_noise, the faster of the two here)")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
                     help="store a and g of a 16-bit workload in this type instead of the workload's own")
     args = ap.parse_args()
@@ -98,6 +101,7 @@ def main():
         layers.append((torch.from_numpy(view(a)).cuda(), torch.from_numpy(view(g)).cuda()))
     pipe = BkPipeline(layers)
     off, cnt = w.noise_range()
+    fused = args.fused_noise
 
     def step(ev=None):
         if ev:
@@ -108,10 +112,14 @@ def main():
         pipe.clip(w.clip_mode, w.R, w.stability)
         if ev:
             ev[2].record()
-        pipe.grad()
+        if fused:
+            pipe.grad_noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+        else:
+            pipe.grad()
         if ev:
             ev[3].record()
-        pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+        if not fused:
+            pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
         if ev:
             ev[4].record()
 
@@ -155,11 +163,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} T={w.T} L={w.L} layers, psi={w.psi}",
                    "clip": "automatic" if w.clip_mode == si.CLIP_AUTOMATIC else "standard",
-                   "R": w.R, "sigma": w.sigma, "noise_elements": cnt},
+                   "R": w.R, "sigma": w.sigma, "noise_elements": cnt,
+                   "noise": "in the gradient kernels' epilogue" if fused else "separate pass"},
         "tflops_nominal": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,
         "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
-        "noise_gbps": 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
+        "noise_gbps": None if fused else 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
         "roofline": {"kernel": "clipped_grad_big_kernel (+ clipped_grad_tail_kernel)" if w.dtype != si.F32
                      else "clipped_grad_f32_kernel",
                      "bound": "mfma",

@@ -180,6 +180,28 @@ dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int 
                                 float* const* grads, int accumulate, void* stream);
 
 /*
+ * dp_clipped_grad_multi with the noise of eq. (1) added in the same pass ("DP gradient" of
+ * section 3 in one step): the result is what dp_clipped_grad_multi followed by dp_add_noise on
+ * the same elements gives, value for value, without the second pass over the gradient.  For
+ * callers whose clipped sums are already final when they are formed: one device, or each rank
+ * adding its own share of the noise before the reduction (the appendix on the user interface).
+ *
+ * Element j of layer l's gradient has global index grad_offset[l] + j; it receives
+ * sigma * R * z_index when shard_offset <= index < shard_offset + shard_count (z as documented
+ * at dp_add_noise: the same generator, seed, step and indexing), and no noise otherwise.
+ *   grad_offset  HOST array of L global element offsets (the layers' places in the flattened
+ *                model; they need not be contiguous or ordered, but must not overlap)
+ *   sigma, R     as dp_add_noise (sigma >= 0, finite; R > 0; sigma == 0 adds nothing)
+ * Layers that the large-tile kernels compute and whose grad_offset is a multiple of 4 get the
+ * noise in the kernel's epilogue; for all others the noise pass runs on the layer's slice
+ * after its gradient.  Errors as dp_clipped_grad_multi and dp_add_noise.
+ */
+dp_status dp_clipped_grad_noise_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                      float* const* grads, const uint64_t* grad_offset, int accumulate,
+                                      uint64_t shard_offset, uint64_t shard_count, float sigma, float R,
+                                      uint64_t seed, uint64_t step, void* stream);
+
+/*
  * Group-wise clipping (eq. (1) with M groups; section 2.1, "Mathematical gradient partition":
  * all-layer clipping is one group, layer-wise clipping one group per layer, the paper's default).
  * The rows of sqnorm (one per layer weight, plus one per bias when biases are trained) are

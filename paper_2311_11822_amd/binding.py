@@ -43,6 +43,8 @@ _PROTOS = {
     "dp_norms_multi_workspace_bytes": (_sz, [C.POINTER(dp_layer), _i, _i, _i]),
     "dp_norms_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, _vp, _sz, _vp]),
     "dp_clipped_grad_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp), _i, _vp]),
+    "dp_clipped_grad_noise_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp),
+                                        C.POINTER(_u64), _i, _u64, _u64, _f, _f, _u64, _u64, _vp]),
     "dp_clip_factors_grouped": (_i, [_vp, _i, _i, C.POINTER(C.c_int32), _i, C.POINTER(_f), _i, _f, _vp, _vp, _vp]),
     "dp_clipped_grad_grouped": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(C.c_int32), _i,
                                      C.POINTER(_vp), _i, _vp]),
@@ -152,6 +154,16 @@ def dp_clipped_grad_multi(layers, dt, B, Cf, grads, accumulate=0, stream=None) -
     gp = grads if isinstance(grads, C.Array) else (C.c_void_p * len(grads))(*[_ptr(x) for x in grads])
     _check(lib.dp_clipped_grad_multi(arr, len(arr), dt, B, _ptr(Cf), gp, accumulate, _stream(stream)),
            "dp_clipped_grad_multi")
+
+
+def dp_clipped_grad_noise_multi(layers, dt, B, Cf, grads, grad_offset, accumulate, shard_offset, shard_count,
+                                sigma, R, seed, step, stream=None) -> None:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    gp = grads if isinstance(grads, C.Array) else (C.c_void_p * len(grads))(*[_ptr(x) for x in grads])
+    offs = grad_offset if isinstance(grad_offset, C.Array) else (C.c_uint64 * len(grad_offset))(*grad_offset)
+    _check(lib.dp_clipped_grad_noise_multi(arr, len(arr), dt, B, _ptr(Cf), gp, offs, accumulate, shard_offset,
+                                           shard_count, sigma, R, seed, step, _stream(stream)),
+           "dp_clipped_grad_noise_multi")
 
 
 def _i32(xs):

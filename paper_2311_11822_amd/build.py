@@ -13,6 +13,10 @@ SOURCES = ["dp_api.hip", "noise.hip", "clip.hip", "fp32_kernels.hip", "ghost.hip
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+# The gradient kernel's epilogue with noise is 16 copies of a large body; beyond the default size
+# limit the compiler stops honouring "#pragma unroll", the accumulator indices stay variable
+# and the 256 accumulators move to scratch memory.
+PER_FILE_FLAGS = {"grad_gemm.hip": ["-mllvm", "-pragma-unroll-threshold=1000000"]}
 
 
 def build(verbose: bool = False) -> str:
@@ -22,7 +26,7 @@ def build(verbose: bool = False) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *PER_FILE_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     objs = []
     for src, obj, proc in procs:

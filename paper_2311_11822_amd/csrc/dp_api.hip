@@ -224,8 +224,26 @@ namespace {
 
 // Clip-weighted gradients of a stack; layer l uses the weights C[c_off[l] + i] (c_off == nullptr:
 // every layer uses C[i]).
+// Noise request of dp_clipped_grad_noise_multi, validated.
+struct NoiseSpec {
+  const uint64_t* grad_offset;   // host, [L]
+  uint64_t lo, hi;               // global element range that receives noise
+  float stddev;
+  uint64_t seed, step;
+};
+
+// Separate noise pass on the part of layer l's gradient that lies inside the range.
+dp_status noise_after(const NoiseSpec* noise, int l, const dp_layer& ly, float* grad, hipStream_t s) {
+  if (!noise) return DP_OK;
+  const uint64_t begin = noise->grad_offset[l], end = begin + (uint64_t)ly.d_in * ly.d_out;
+  const uint64_t lo = std::max(begin, noise->lo), hi = std::min(end, noise->hi);
+  if (lo >= hi) return DP_OK;
+  return launch_noise(grad + (lo - begin), lo, hi - lo, noise->stddev, noise->seed, noise->step, s);
+}
+
 dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
-                            const int* c_off, float* const* grads, int accumulate, void* stream) {
+                            const int* c_off, float* const* grads, int accumulate, void* stream,
+                            const NoiseSpec* noise = nullptr) {
   if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!layers || !grads || !C || L <= 0 || B <= 0) return DP_ERR_INVALID_ARG;
   if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
@@ -243,6 +261,8 @@ dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, c
                                              static_cast<const float*>(layers[l].g), B, layers[l].T,
                                              layers[l].d_in, layers[l].d_out, C + (c_off ? c_off[l] : 0),
                                              grads[l], accumulate, s);
+      if (st != DP_OK) return st;
+      st = noise_after(noise, l, layers[l], grads[l], s);
       if (st != DP_OK) return st;
     }
     return DP_OK;
@@ -287,8 +307,35 @@ dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, c
         ++pos;
       }
       ga.total_blocks = (int)blocks;
-      dp_status st = pass == 0 ? launch_clipped_grad_big_group(ga, C, s) : launch_clipped_grad_group(ga, C, s);
+      // The large-tile kernels add the noise in their epilogue when every layer of the launch
+      // starts on a generator block (offset a multiple of 4); otherwise, and for the small-layer
+      // kernel, the noise pass runs on the layer's slice afterwards.
+      bool fused = noise && pass == 0;
+      NoiseArgs na;
+      if (fused) {
+        for (int j = 0; j < ga.n_layers; ++j) {
+          na.layer_off[j] = noise->grad_offset[ga.layer[j].sq_index];
+          fused = fused && (na.layer_off[j] & 3) == 0;
+        }
+      }
+      if (fused) {
+        na.stddev = noise->stddev;
+        na.step_lo = (uint32_t)noise->step;
+        na.step_hi = (uint32_t)(noise->step >> 32);
+        na.lo = noise->lo;
+        na.hi = noise->hi;
+        na.rk = make_round_keys(noise->seed);
+      }
+      dp_status st = pass == 0 ? launch_clipped_grad_big_group(ga, C, fused ? &na : nullptr, s)
+                               : launch_clipped_grad_group(ga, C, s);
       if (st != DP_OK) return st;
+      if (noise && !fused) {
+        for (int j = 0; j < ga.n_layers; ++j) {
+          const int l = ga.layer[j].sq_index;
+          st = noise_after(noise, l, layers[l], grads[l], s);
+          if (st != DP_OK) return st;
+        }
+      }
     }
   }
   return DP_OK;
@@ -301,6 +348,30 @@ extern "C" {
 dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
                                 float* const* grads, int accumulate, void* stream) {
   return clipped_grad_impl(layers, L, dt, B, C, nullptr, grads, accumulate, stream);
+}
+
+dp_status dp_clipped_grad_noise_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                      float* const* grads, const uint64_t* grad_offset, int accumulate,
+                                      uint64_t shard_offset, uint64_t shard_count, float sigma, float R,
+                                      uint64_t seed, uint64_t step, void* stream) {
+  if (!(sigma >= 0.f) || isinf(sigma)) return DP_ERR_INVALID_ARG;
+  if (!(R > 0.f)) return DP_ERR_INVALID_ARG;
+  if (shard_offset + shard_count < shard_offset) return DP_ERR_INVALID_ARG;   // wraps 2^64
+  if (sigma == 0.f || shard_count == 0)                                        // nothing to add
+    return clipped_grad_impl(layers, L, dt, B, C, nullptr, grads, accumulate, stream);
+  if (isinf(R) || !grad_offset || !layers || L <= 0) return DP_ERR_INVALID_ARG;
+  for (int l = 0; l < L; ++l) {
+    const uint64_t n = (uint64_t)std::max(layers[l].d_in, 0) * (uint64_t)std::max(layers[l].d_out, 0);
+    if (grad_offset[l] + n < grad_offset[l]) return DP_ERR_INVALID_ARG;
+  }
+  NoiseSpec spec;
+  spec.grad_offset = grad_offset;
+  spec.lo = shard_offset;
+  spec.hi = shard_offset + shard_count;
+  spec.stddev = sigma * R;
+  spec.seed = seed;
+  spec.step = step;
+  return clipped_grad_impl(layers, L, dt, B, C, nullptr, grads, accumulate, stream, &spec);
 }
 
 dp_status dp_clipped_grad_grouped(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "dp_bk.h"
+#include "philox.h"
 
 namespace dpbk {
 
@@ -53,6 +54,17 @@ struct GroupArgs {
   GroupLayer layer[kMaxGroup];
 };
 
+// Noise added in the epilogue of the large-tile gradient kernels (eq. (1) of the paper):
+// element j of layer l's gradient has global index layer_off[l] + j and receives
+// stddev * z_index when lo <= index < hi.  stddev == 0 switches the noise off.
+struct NoiseArgs {
+  float stddev;
+  uint32_t step_lo, step_hi;
+  uint64_t lo, hi;
+  RoundKeys rk;
+  uint64_t layer_off[kMaxGroup];
+};
+
 inline dp_status hip_status(hipError_t e) { return e == hipSuccess ? DP_OK : DP_ERR_HIP; }
 
 // --- launchers implemented in the .hip files (all validate nothing; callers did) ---
@@ -93,6 +105,8 @@ dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream
 // 256x256-tile kernel with direct global->LDS loads (grad_gemm.hip).
 int clipped_grad_big_tiles(int d, int p);
 bool clipped_grad_big_supports(int T, int d, int p);
-dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, hipStream_t s);
+// noise == nullptr: gradients only.
+dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, const NoiseArgs* noise,
+                                        hipStream_t s);
 
 }  // namespace dpbk

@@ -110,9 +110,74 @@ __device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& lay
   n0 = (16 * sc + 8 * pc + rem / ph) * BN;
 }
 
-template <bool F16>
+// Adds the noise of eq. (1) to one 32 x 32 output tile held by a wave in the MFMA result layout
+// (lane: column lane & 31, rows 8 (r >> 2) + 4 (lane >> 5) + (r & 3), r = 0 .. 15).  A generator
+// block covers four consecutive columns of one row, a lane holds single columns, so the wave
+// first writes the tile's 256 blocks of normals (four per lane) to its 4 KiB of LDS in row-major
+// order and every lane then picks up the 16 values it needs.  LDS operations of one wave
+// execute in order, so no barrier is needed between the two steps; the wave barriers only keep
+// the compiler from reordering them.  Same values as the separate noise pass: both index the
+// generator by global element.  Requires layer_off and d_out to be multiples of 4.
+// The kernel's copy of what tile_noise needs, read once from the kernel arguments into registers.
+struct TileNoise {
+  float stddev;
+  uint32_t step_lo, step_hi;
+  uint64_t lo, hi, layer_off;
+  RoundKeys rk;
+};
+
+__device__ __forceinline__ TileNoise load_tile_noise(const NoiseArgs& na, int layer) {
+  TileNoise t;
+  t.stddev = na.stddev;
+  t.step_lo = na.step_lo;
+  t.step_hi = na.step_hi;
+  t.lo = na.lo;
+  t.hi = na.hi;
+  t.layer_off = na.layer_off[layer];
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    t.rk.k[r][0] = na.rk.k[r][0];
+    t.rk.k[r][1] = na.rk.k[r][1];
+  }
+  return t;
+}
+
+__device__ __forceinline__ void tile_noise(float (&v)[16], const TileNoise na, int row0, int col0, int d, int p,
+                                           float* zbuf, int lane) {
+  const uint64_t layer_off = na.layer_off;
+  const int rows = min(32, d - row0), cols = min(32, p - col0);
+  if (rows <= 0 || cols <= 0) return;
+  const uint64_t e_first = layer_off + (uint64_t)row0 * p + col0;
+  const uint64_t e_last = layer_off + (uint64_t)(row0 + rows - 1) * p + (col0 + cols - 1);
+  if (e_last < na.lo || e_first >= na.hi) return;               // wave-uniform: tile outside the shard
+  const bool whole = e_first >= na.lo && e_last < na.hi;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = lane + 64 * j, trow = b >> 3, cg = b & 7;
+    const int r_abs = row0 + trow, c_abs = col0 + 4 * cg;
+    float z[4] = {0.f, 0.f, 0.f, 0.f};
+    if (r_abs < d && c_abs < p)
+      normal_block((layer_off + (uint64_t)r_abs * p + c_abs) >> 2, na.step_lo, na.step_hi, na.rk, z);
+    *reinterpret_cast<float4*>(zbuf + trow * 32 + 4 * cg) = make_float4(z[0], z[1], z[2], z[3]);
+  }
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int trow = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), tcol = lane & 31;
+    const float z = zbuf[trow * 32 + tcol];
+    bool in = true;
+    if (!whole) {
+      const uint64_t e = layer_off + (uint64_t)(row0 + trow) * p + (col0 + tcol);
+      in = e >= na.lo && e < na.hi;
+    }
+    if (in) v[r] = fmaf(na.stddev, z, v[r]);
+  }
+  __builtin_amdgcn_wave_barrier();
+}
+
+template <bool F16, bool NOISE>
 __global__ void __launch_bounds__(NT)
-clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) {
+clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, const NoiseArgs na) {
   // The weights do not change during the kernel: read them through the constant address space
   // so that they come by scalar loads (a vector load here would make the compiler wait for
   // every outstanding prefetch load at each sample boundary).
@@ -343,8 +408,15 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // zero-fill loads past the end
   }
 
-  // epilogue: grad (+)= held * acc.  With no active sample the accumulator is zero.
+  // epilogue: grad (+)= held * acc (+ noise).  With no active sample the accumulator is zero.
   float* out = ly.out;
+  float* zbuf = nullptr;
+  TileNoise tn = {};
+  if (NOISE) {
+    __syncthreads();                 // every wave is done with the stages; their LDS is free
+    zbuf = reinterpret_cast<float*>(lds_raw) + wave * 1024;
+    tn = load_tile_noise(na, l);
+  }
   auto store_tile = [&](auto acc_tag) {
     constexpr bool accumulate = decltype(acc_tag)::value;
 #pragma unroll
@@ -361,11 +433,17 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global) 
             old[r] = (row < d && col < p) ? base[(size_t)(8 * (r >> 2) + (r & 3)) * p] : 0.f;
           }
         }
+        float v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float t = acc[x][y][r] * held;
+          v[r] = accumulate ? old[r] + t : t;
+        }
+        if (NOISE) tile_noise(v, tn, m0 + wm + x * 32, n0 + wn + y * 32, d, p, zbuf, lane);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = m0 + wm + x * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          const float v = acc[x][y][r] * held;
-          if (row < d && col < p) base[(size_t)(8 * (r >> 2) + (r & 3)) * p] = accumulate ? old[r] + v : v;
+          if (row < d && col < p) base[(size_t)(8 * (r >> 2) + (r & 3)) * p] = v[r];
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -403,9 +481,9 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 // conditional: the number of loads in flight is a compile-time constant and a thread waits only
 // for the slot it is about to store.  Two LDS stages, one barrier per k-block.  The k-steps of an output element are added in
 // the same order as in the large kernel.
-template <class S, int D, bool F16>
+template <class S, int D, bool F16, bool NOISE>
 __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int B, int accumulate,
-                                                       int m0, int n0,
+                                                       const NoiseArgs& na, int layer, int m0, int n0,
                                                        const __attribute__((address_space(4))) float* C,
                                                        uint16_t* lds) {
   static_assert(D % 2 == 0, "the LDS stage of slot q is q & 1");
@@ -437,7 +515,7 @@ __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int
   // All operand fragments of a k-block are requested from LDS before its first MFMA, so one LDS
   // latency is exposed per k-block instead of one per MFMA (a wave has nothing else to run).
   static_assert(S::TM == 1 && S::TN == 1, "one 32 x 32 MFMA tile per wave");
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / S::WN) * S::WTM, wn = (wave % S::WN) * S::WTN;
   auto compute = [&](const uint16_t* stage, f32x16& c) {
     constexpr int KS = S::BK / 16;
@@ -528,21 +606,24 @@ __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int
   }
 
   float* out = ly.out;
+  const int col = n0 + wn + (lane & 31);
+  float v[16];
 #pragma unroll
-  for (int im = 0; im < S::TM; ++im)
+  for (int r = 0; r < 16; ++r) {
+    const int row = m0 + wm + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    const float t = acc[0][0][r] * held;
+    v[r] = (accumulate && row < d && col < p) ? out[(size_t)row * p + col] + t : t;
+  }
+  if (NOISE) {
+    __syncthreads();                 // every wave is done with the stages; their LDS is free
+    tile_noise(v, load_tile_noise(na, layer), m0 + wm, n0 + wn, d, p, reinterpret_cast<float*>(lds) + wave * 1024,
+               lane);
+  }
 #pragma unroll
-    for (int jn = 0; jn < S::TN; ++jn) {
-      const int col = n0 + wn + jn * 32 + (lane & 31);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm + im * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < d && col < p) {
-          float* dst = out + (size_t)row * p + col;
-          const float v = acc[im][jn][r] * held;
-          *dst = accumulate ? *dst + v : v;
-        }
-      }
-    }
+  for (int r = 0; r < 16; ++r) {
+    const int row = m0 + wm + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    if (row < d && col < p) out[(size_t)row * p + col] = v[r];
+  }
 }
 
 // Sub-tiles are 64 x 64 (16 per tile), k-blocks of 64 rows, four k-blocks in flight: three
@@ -551,9 +632,10 @@ using TailShape = TnShape<DP_TAIL_SHAPE>;
 constexpr int TAIL = 64, SUBS_N = BN / TAIL, SUBS = (BM / TAIL) * SUBS_N;
 static_assert(TailShape::BM == TAIL && TailShape::BN == TAIL, "sub-tile shape");
 
-template <bool F16>
+template <bool F16, bool NOISE>
 __global__ void __launch_bounds__(TailShape::NT)
-clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, int first_tile) {
+clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, int first_tile,
+                         const NoiseArgs na) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_tail[];
   // Workgroup b runs on XCD b % 8: give each XCD a contiguous eighth of the sub-tiles (the grid
   // is a multiple of 16), so that the 16 sub-tiles of a tile, which share its operand panels,
@@ -568,7 +650,8 @@ clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, in
   if (m0 >= ly.d_in || n0 >= ly.d_out) return;       // sub-tile past the layer's edge (whole workgroup)
   const __attribute__((address_space(4))) float* C =
       (const __attribute__((address_space(4))) float*)(uintptr_t)(C_all + ly.c_off);
-  clipped_grad_tile_deep<TailShape, DP_TAIL_DEPTH, F16>(ly, ga.B, ga.accumulate, m0, n0, C, lds_tail);
+  clipped_grad_tile_deep<TailShape, DP_TAIL_DEPTH, F16, NOISE>(ly, ga.B, ga.accumulate, na, l, m0,
+                                                               n0, C, lds_tail);
 }
 
 }  // namespace
@@ -592,10 +675,11 @@ bool clipped_grad_big_supports(int T, int d, int p) {
 #endif
 constexpr int kRound = 256;           // compute units = large-tile workgroups resident at a time
 
-template <bool F16>
-dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, hipStream_t s) {
-  auto big = clipped_grad_big_kernel<F16>;
-  auto tail = clipped_grad_tail_kernel<F16>;
+template <bool F16, bool NOISE>
+dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, const NoiseArgs& na,
+                                          hipStream_t s) {
+  auto big = clipped_grad_big_kernel<F16, NOISE>;
+  auto tail = clipped_grad_tail_kernel<F16, NOISE>;
   static bool ready = false;
   if (!ready) {
     dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(big),
@@ -613,19 +697,25 @@ dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, h
   if (n > n_tail) {
     GroupArgs main_args = ga;
     main_args.total_blocks = n - n_tail;
-    hipLaunchKernelGGL(big, dim3(n - n_tail), dim3(NT), LDS_BYTES, s, main_args, C);
+    hipLaunchKernelGGL(big, dim3(n - n_tail), dim3(NT), LDS_BYTES, s, main_args, C, na);
     dp_status st = hip_status(hipGetLastError());
     if (st != DP_OK) return st;
   }
   if (n_tail == 0) return DP_OK;
   hipLaunchKernelGGL(tail, dim3(n_tail * SUBS), dim3(TailShape::NT), TailShape::LDS_BYTES, s, ga, C,
-                     n - n_tail);
+                     n - n_tail, na);
   return hip_status(hipGetLastError());
 }
 
-dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, hipStream_t s) {
-  return ga.f16 ? launch_clipped_grad_big_group_t<true>(ga, C, s)
-                : launch_clipped_grad_big_group_t<false>(ga, C, s);
+dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, const NoiseArgs* noise,
+                                        hipStream_t s) {
+  if (noise) {
+    return ga.f16 ? launch_clipped_grad_big_group_t<true, true>(ga, C, *noise, s)
+                  : launch_clipped_grad_big_group_t<false, true>(ga, C, *noise, s);
+  }
+  static const NoiseArgs none = {};
+  return ga.f16 ? launch_clipped_grad_big_group_t<true, false>(ga, C, none, s)
+                : launch_clipped_grad_big_group_t<false, false>(ga, C, none, s);
 }
 
 }  // namespace dpbk

@@ -37,6 +37,11 @@ class BkPipeline:
             self.grads.append(self.flat[off:off + d * p].view(d, p))
             off += d * p
         self.grad_ptrs = (dp.C.c_void_p * L)(*[x.data_ptr() for x in self.grads])
+        offs, acc = [], 0
+        for _, d, p in self.dims:
+            offs.append(acc)
+            acc += d * p
+        self.grad_offsets = (dp.C.c_uint64 * L)(*offs)
         ws_bytes = dp.dp_norms_multi_workspace_bytes(self.desc, self.dt, self.B)
         if ws_bytes == 0:
             raise dp.DpError(dp.DP_ERR_INVALID_ARG, "dp_norms_multi_workspace_bytes")
@@ -51,11 +56,20 @@ class BkPipeline:
     def grad(self, accumulate=0, stream=None):
         dp.dp_clipped_grad_multi(self.desc, self.dt, self.B, self.C, self.grad_ptrs, accumulate, stream)
 
+    def grad_noise(self, sigma, R, seed, step, offset, count, accumulate=0, stream=None):
+        """Gradients with the noise added in the same pass (elements [offset, offset + count) of
+        the flattened gradient)."""
+        dp.dp_clipped_grad_noise_multi(self.desc, self.dt, self.B, self.C, self.grad_ptrs, self.grad_offsets,
+                                       accumulate, offset, count, sigma, R, seed, step, stream)
+
     def noise(self, sigma, R, seed, step, offset, count, stream=None):
         dp.dp_add_noise(self.flat.data_ptr() + 4 * offset, offset, count, sigma, R, seed, step, stream)
 
-    def step(self, mode, R, sigma, stability, seed, step, offset, count, stream=None):
+    def step(self, mode, R, sigma, stability, seed, step, offset, count, stream=None, fused=False):
         self.norms(stream)
         self.clip(mode, R, stability, stream)
-        self.grad(0, stream)
-        self.noise(sigma, R, seed, step, offset, count, stream)
+        if fused:
+            self.grad_noise(sigma, R, seed, step, offset, count, 0, stream)
+        else:
+            self.grad(0, stream)
+            self.noise(sigma, R, seed, step, offset, count, stream)

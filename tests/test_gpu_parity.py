@@ -372,6 +372,11 @@ def run_workload(dp, Pipe, name, full_layers=()):
         assert torch.equal(pipe.flat[off + cnt:], before[off + cnt:])
         delta = (pipe.flat[off:off + cnt] - before[off:off + cnt]).double()
         assert abs(float(delta.std()) / std - 1) < 1e-3
+    # the same step with the noise added in the gradient kernels' epilogue: value for value
+    two_pass = pipe.flat.clone()
+    pipe.flat.fill_(7.0)
+    pipe.grad_noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+    assert torch.equal(pipe.flat, two_pass)
     return pipe
 
 
@@ -501,6 +506,74 @@ def test_layerwise_clipping_with_biases(dp, dtype):
 # ----------------------------------------------------------------------------
 
 # ----------------------------------------------------------------------------
+# gradient + noise in one pass (dp_clipped_grad_noise_multi)
+# ----------------------------------------------------------------------------
+
+FUSED_CASES = [
+    # dtype, B, T, dims, gaps (elements skipped before each layer in the flattened model), base offset
+    (si.BF16, 3, 96, [(136, 264), (264, 136), (392, 520), (8, 16)], [0, 0, 0, 0], 0),
+    (si.BF16, 3, 96, [(136, 264), (264, 136), (392, 520), (8, 16)], [0, 3, 0, 8], 1 << 34),   # 2nd, 3rd start off a block
+    (si.F16, 2, 64, [(1800, 1544), (128, 128)], [4, 0], 12),
+    (si.BF16, 2, 32, [(4360, 3848)], [0], 0),                    # large tiles and sub-tiles in one launch
+    (si.BF16, 2, 50, [(136, 264), (264, 136)], [0, 0], 0),       # T not a multiple of 32: small-layer kernel
+    (si.F32, 3, 5, [(8, 12), (12, 4)], [0, 1], 0),
+]
+
+
+@pytest.mark.parametrize("accumulate", [0, 1])
+@pytest.mark.parametrize("dtype,B,T,dims,gaps,base", FUSED_CASES)
+def test_fused_noise_equals_two_passes(dp, dtype, B, T, dims, gaps, base, accumulate):
+    w = si.small_workload("fz", dtype, B, T, dims)
+    layers = gen(w)
+    dt = dt_of(dp, dtype)
+    desc = [(dev(a), dev(g), T, d, p, dp.dp_choose_path(T, d, p)) for (a, g), (d, p) in zip(layers, dims)]
+    C = np.random.default_rng(8).uniform(0.1, 1.0, B).astype(np.float32)
+    if B > 2:
+        C[1] = 0.0
+    Cd = dev(C)
+    offs, acc = [], 0
+    for (d, p), gap in zip(dims, gaps):
+        acc += gap
+        offs.append(acc)
+        acc += d * p
+    total = acc
+    sigma, R, seed, step = 0.7, 1.5, 0xABCDEF0123, 5
+
+    def buffers():
+        # device layout: one 16-byte aligned buffer per layer, whatever its global offset
+        return [torch.full((d, p), 0.25, dtype=torch.float32, device="cuda") for d, p in dims]
+
+    shards = [(0, total), (1001 % total, max(1, total // 3)), (total - 1, 1), (total + 5, 10), (3, 0)]
+    for s_off, s_cnt in shards:
+        lo, hi = base + s_off, base + s_off + s_cnt
+        ref = buffers()
+        dp.dp_clipped_grad_multi(desc, dt, B, Cd, ref, accumulate)
+        for (d, p), o_l, buf in zip(dims, offs, ref):
+            b0, b1 = base + o_l, base + o_l + d * p
+            x0, x1 = max(b0, lo), min(b1, hi)
+            if x0 < x1:
+                flat = buf.view(-1)
+                dp.dp_add_noise(flat.data_ptr() + 4 * (x0 - b0), x0, x1 - x0, sigma, R, seed, step)
+        got = buffers()
+        dp.dp_clipped_grad_noise_multi(desc, dt, B, Cd, got, [base + o_l for o_l in offs], accumulate,
+                                       lo, s_cnt, sigma, R, seed, step)
+        for l, (x, y) in enumerate(zip(got, ref)):
+            assert torch.equal(x, y), (l, s_off, s_cnt, float((x - y).abs().max()))
+    # and against the oracle: noise values at the global indices, gradient from the definition
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    got = buffers()
+    dp.dp_clipped_grad_noise_multi(desc, dt, B, Cd, got, [base + o_l for o_l in offs], 0, base, total,
+                                   sigma, R, seed, step)
+    for (a, g), (d, p), o_l, buf in zip(l64, dims, offs, got):
+        G = o.clipped_grad(a, g, C.astype(np.float64))
+        n_chk = min(d * p, 5000)
+        z = o.normals(seed, step, base + o_l, n_chk)
+        want = G.reshape(-1)[:n_chk] + sigma * R * z
+        have = host(buf).reshape(-1)[:n_chk]
+        assert np.all(np.abs(have - want) <= 2e-5 * sigma * R * np.maximum(1.0, np.abs(z)) + 1e-4 * np.abs(G.reshape(-1)[:n_chk]))
+
+
+# ----------------------------------------------------------------------------
 # fp16 inputs without loss scaling (section 3.4 and the loss-scaling table)
 # ----------------------------------------------------------------------------
 
@@ -580,5 +653,13 @@ def test_argument_errors(dp):
     assert lib.dp_add_noise(None, 0, 16, 1.0, 1.0, 0, 0, None) == INV
     assert lib.dp_add_noise(p, 2 ** 64 - 4, 16, 1.0, 1.0, 0, 0, None) == INV
     assert lib.dp_add_noise(p, 0, 0, 1.0, 1.0, 0, 0, None) == dp.DP_OK
+    import ctypes
+    arr = dp.layer_array([(p, p, 8, 8, 8, 0)])
+    gp = (ctypes.c_void_p * 1)(p + 8192)
+    offs = (ctypes.c_uint64 * 1)(0)
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, p, gp, None, 0, 0, 16, 1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, p, gp, offs, 0, 0, 16, -1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, p, gp, offs, 0, 2 ** 64 - 4, 16, 1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, p, gp, offs, 0, 0, 16, 1.0, float("inf"), 0, 0, None) == INV
     torch.cuda.synchronize()
     assert not host(x).any()
