@@ -71,9 +71,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg1", choices=sorted(si.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--fused-noise", action="store_true",
-                    help="add the noise in the gradient kernels' epilogue (dp_clipped_grad_noise_multi) "
-                         "instead of in a pass of its own (dp_add_noise, the faster of the two here)")
+    ap.add_argument("--separate-noise", action="store_true",
+                    help="add the noise in a pass of its own (dp_add_noise) instead of in the gradient "
+                         "kernels' epilogue (dp_clipped_grad_noise_multi, the faster of the two)")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
                     help="store a and g of a 16-bit workload in this type instead of the workload's own")
     args = ap.parse_args()
@@ -101,7 +101,7 @@ def main():
         layers.append((torch.from_numpy(view(a)).cuda(), torch.from_numpy(view(g)).cuda()))
     pipe = BkPipeline(layers)
     off, cnt = w.noise_range()
-    fused = args.fused_noise
+    fused = not args.separate_noise
 
     def step(ev=None):
         if ev:

@@ -33,6 +33,7 @@ namespace dpbk {
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4v;
 
 #ifndef DP_GRAD_NSTAGE
 #define DP_GRAD_NSTAGE 5
@@ -110,14 +111,6 @@ __device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& lay
   n0 = (16 * sc + 8 * pc + rem / ph) * BN;
 }
 
-// Adds the noise of eq. (1) to one 32 x 32 output tile held by a wave in the MFMA result layout
-// (lane: column lane & 31, rows 8 (r >> 2) + 4 (lane >> 5) + (r & 3), r = 0 .. 15).  A generator
-// block covers four consecutive columns of one row, a lane holds single columns, so the wave
-// first writes the tile's 256 blocks of normals (four per lane) to its 4 KiB of LDS in row-major
-// order and every lane then picks up the 16 values it needs.  LDS operations of one wave
-// execute in order, so no barrier is needed between the two steps; the wave barriers only keep
-// the compiler from reordering them.  Same values as the separate noise pass: both index the
-// generator by global element.  Requires layer_off and d_out to be multiples of 4.
 // The kernel's copy of what tile_noise needs, read once from the kernel arguments into registers.
 struct TileNoise {
   float stddev;
@@ -142,37 +135,37 @@ __device__ __forceinline__ TileNoise load_tile_noise(const NoiseArgs& na, int la
   return t;
 }
 
-__device__ __forceinline__ void tile_noise(float (&v)[16], const TileNoise na, int row0, int col0, int d, int p,
-                                           float* zbuf, int lane) {
-  const uint64_t layer_off = na.layer_off;
-  const int rows = min(32, d - row0), cols = min(32, p - col0);
+// Output layout.  The MFMAs take the g fragment as first operand and the a fragment as second,
+// so a wave holds the transposed product: lane l has row (l & 31) of a 32 x 32 output tile and
+// the columns 8 q + 4 (l >> 5) + e (q, e = 0 .. 3) in register 4 q + e: four runs of four
+// consecutive columns, which are stored as 16-byte vectors (a quarter of the store
+// instructions of the untransposed layout, whose lanes hold single columns) and each of which
+// is exactly one block of the noise generator.
+//
+// Adds the noise of eq. (1) to the lane's 16 values of the tile at (tile_row0, tile_col0): same
+// values as the separate noise pass, which indexes the generator by global element too.
+// Requires layer_off and d_out to be multiples of 4.
+__device__ __forceinline__ void tile_noise(float (&v)[16], const TileNoise& na, int tile_row0, int tile_col0,
+                                           int d, int p, int lane) {
+  const int rows = min(32, d - tile_row0), cols = min(32, p - tile_col0);
   if (rows <= 0 || cols <= 0) return;
-  const uint64_t e_first = layer_off + (uint64_t)row0 * p + col0;
-  const uint64_t e_last = layer_off + (uint64_t)(row0 + rows - 1) * p + (col0 + cols - 1);
+  const uint64_t e_first = na.layer_off + (uint64_t)tile_row0 * p + tile_col0;
+  const uint64_t e_last = na.layer_off + (uint64_t)(tile_row0 + rows - 1) * p + (tile_col0 + cols - 1);
   if (e_last < na.lo || e_first >= na.hi) return;               // wave-uniform: tile outside the shard
   const bool whole = e_first >= na.lo && e_last < na.hi;
+  const int row = tile_row0 + (lane & 31);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int b = lane + 64 * j, trow = b >> 3, cg = b & 7;
-    const int r_abs = row0 + trow, c_abs = col0 + 4 * cg;
-    float z[4] = {0.f, 0.f, 0.f, 0.f};
-    if (r_abs < d && c_abs < p)
-      normal_block((layer_off + (uint64_t)r_abs * p + c_abs) >> 2, na.step_lo, na.step_hi, na.rk, z);
-    *reinterpret_cast<float4*>(zbuf + trow * 32 + 4 * cg) = make_float4(z[0], z[1], z[2], z[3]);
-  }
-  __builtin_amdgcn_wave_barrier();
+  for (int q = 0; q < 4; ++q) {
+    const int col = tile_col0 + 8 * q + 4 * (lane >> 5);
+    if (row < d && col < p) {
+      const uint64_t e = na.layer_off + (uint64_t)row * p + col;
+      float z[4];
+      normal_block(e >> 2, na.step_lo, na.step_hi, na.rk, z);
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int trow = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), tcol = lane & 31;
-    const float z = zbuf[trow * 32 + tcol];
-    bool in = true;
-    if (!whole) {
-      const uint64_t e = layer_off + (uint64_t)(row0 + trow) * p + (col0 + tcol);
-      in = e >= na.lo && e < na.hi;
+      for (int k = 0; k < 4; ++k)
+        if (whole || (e + k >= na.lo && e + k < na.hi)) v[4 * q + k] = fmaf(na.stddev, z[k], v[4 * q + k]);
     }
-    if (in) v[r] = fmaf(na.stddev, z, v[r]);
   }
-  __builtin_amdgcn_wave_barrier();
 }
 
 template <bool F16, bool NOISE>
@@ -335,22 +328,22 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, 
         const int r_stage = ks == 0 ? c_stage : n_stage, r_ks = ks == 0 ? 1 : 0;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          acc[g][0] = mfma16<F16>(fa[cb][g].v, fb[cb][0].v, acc[g][0]);
+          acc[g][0] = mfma16<F16>(fb[cb][0].v, fa[cb][g].v, acc[g][0]);
           DP_PIN();
           if (fetch) read_frag(nb, 2 * g, r_stage, r_ks);
           DP_PIN();
-          acc[g][1] = mfma16<F16>(fa[cb][g].v, fb[cb][1].v, acc[g][1]);
+          acc[g][1] = mfma16<F16>(fb[cb][1].v, fa[cb][g].v, acc[g][1]);
           DP_PIN();
           if (fetch) read_frag(nb, 2 * g + 1, r_stage, r_ks);
           DP_PIN();
-          acc[g][2] = mfma16<F16>(fa[cb][g].v, fb[cb][2].v, acc[g][2]);
+          acc[g][2] = mfma16<F16>(fb[cb][2].v, fa[cb][g].v, acc[g][2]);
           DP_PIN();
           if (g & 1)
             prefetch_issue_b(ks * 2 + (g >> 1));
           else
             prefetch_issue_a(ks * 2 + (g >> 1));
           DP_PIN();
-          acc[g][3] = mfma16<F16>(fa[cb][g].v, fb[cb][3].v, acc[g][3]);
+          acc[g][3] = mfma16<F16>(fb[cb][3].v, fa[cb][g].v, acc[g][3]);
           DP_PIN();
         }
       }
@@ -408,43 +401,38 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // zero-fill loads past the end
   }
 
-  // epilogue: grad (+)= held * acc (+ noise).  With no active sample the accumulator is zero.
+  // epilogue: grad (+)= held * acc (+ noise), in the transposed layout described at tile_noise.
+  // With no active sample the accumulator is zero.
   float* out = ly.out;
-  float* zbuf = nullptr;
   TileNoise tn = {};
-  if (NOISE) {
-    __syncthreads();                 // every wave is done with the stages; their LDS is free
-    zbuf = reinterpret_cast<float*>(lds_raw) + wave * 1024;
-    tn = load_tile_noise(na, l);
-  }
+  if (NOISE) tn = load_tile_noise(na, l);
   auto store_tile = [&](auto acc_tag) {
     constexpr bool accumulate = decltype(acc_tag)::value;
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
       for (int y = 0; y < 4; ++y) {
-        const int col = n0 + wn + y * 32 + (lane & 31);
-        float* base = out + (size_t)(m0 + wm + x * 32 + 4 * (lane >> 5)) * p + col;
-        float old[16];
-        if (accumulate) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm + x * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            old[r] = (row < d && col < p) ? base[(size_t)(8 * (r >> 2) + (r & 3)) * p] : 0.f;
-          }
-        }
+        const int row = m0 + wm + x * 32 + (lane & 31);
+        const int col0 = n0 + wn + y * 32 + 4 * (lane >> 5);
+        f32x4v* base = reinterpret_cast<f32x4v*>(out + (size_t)row * p + col0);   // + 2 q: columns col0 + 8 q ..
         float v[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float t = acc[x][y][r] * held;
-          v[r] = accumulate ? old[r] + t : t;
-        }
-        if (NOISE) tile_noise(v, tn, m0 + wm + x * 32, n0 + wn + y * 32, d, p, zbuf, lane);
+        for (int q = 0; q < 4; ++q) {
+          f32x4v old = {0.f, 0.f, 0.f, 0.f};
+          if (accumulate && row < d && col0 + 8 * q < p) old = base[2 * q];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm + x * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (row < d && col < p) base[(size_t)(8 * (r >> 2) + (r & 3)) * p] = v[r];
+          for (int k = 0; k < 4; ++k) {
+            const float t = acc[x][y][4 * q + k] * held;
+            v[4 * q + k] = accumulate ? old[k] + t : t;
+          }
         }
+        if (NOISE) tile_noise(v, tn, m0 + wm + x * 32, n0 + wn + y * 32, d, p, lane);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (row < d && col0 + 8 * q < p) {
+            const f32x4v w = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+            base[2 * q] = w;
+          }
         __builtin_amdgcn_sched_barrier(0);
       }
   };
@@ -527,7 +515,7 @@ __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) c = mfma16<F16>(fa[ks], fb[ks], c);
+    for (int ks = 0; ks < KS; ++ks) c = mfma16<F16>(fb[ks], fa[ks], c);
   };
   u32x4 sa[D][S::A_PER_T], sb[D][S::B_PER_T];
   f32x16 acc[S::TM][S::TN];
@@ -605,25 +593,28 @@ __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int
     }
   }
 
+  // epilogue in the transposed layout described at tile_noise
   float* out = ly.out;
-  const int col = n0 + wn + (lane & 31);
+  const int row = m0 + wm + (lane & 31), col0 = n0 + wn + 4 * (lane >> 5);
+  f32x4v* base = reinterpret_cast<f32x4v*>(out + (size_t)row * p + col0);
   float v[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = m0 + wm + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    const float t = acc[0][0][r] * held;
-    v[r] = (accumulate && row < d && col < p) ? out[(size_t)row * p + col] + t : t;
-  }
-  if (NOISE) {
-    __syncthreads();                 // every wave is done with the stages; their LDS is free
-    tile_noise(v, load_tile_noise(na, layer), m0 + wm, n0 + wn, d, p, reinterpret_cast<float*>(lds) + wave * 1024,
-               lane);
-  }
+  for (int q = 0; q < 4; ++q) {
+    f32x4v old = {0.f, 0.f, 0.f, 0.f};
+    if (accumulate && row < d && col0 + 8 * q < p) old = base[2 * q];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = m0 + wm + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    if (row < d && col < p) out[(size_t)row * p + col] = v[r];
+    for (int k = 0; k < 4; ++k) {
+      const float t = acc[0][0][4 * q + k] * held;
+      v[4 * q + k] = accumulate ? old[k] + t : t;
+    }
   }
+  if (NOISE) tile_noise(v, load_tile_noise(na, layer), m0 + wm, n0 + wn, d, p, lane);
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (row < d && col0 + 8 * q < p) {
+      const f32x4v w = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+      base[2 * q] = w;
+    }
 }
 
 // Sub-tiles are 64 x 64 (16 per tile), k-blocks of 64 rows, four k-blocks in flight: three

@@ -65,7 +65,7 @@ class BkPipeline:
     def noise(self, sigma, R, seed, step, offset, count, stream=None):
         dp.dp_add_noise(self.flat.data_ptr() + 4 * offset, offset, count, sigma, R, seed, step, stream)
 
-    def step(self, mode, R, sigma, stability, seed, step, offset, count, stream=None, fused=False):
+    def step(self, mode, R, sigma, stability, seed, step, offset, count, stream=None, fused=True):
         self.norms(stream)
         self.clip(mode, R, stability, stream)
         if fused:
