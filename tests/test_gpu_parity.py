@@ -273,6 +273,32 @@ def test_bf16_clipped_grad(dp, B, T, d, p, dtype):
     assert not host(grad).any()
 
 
+@pytest.mark.parametrize("B,T,d,p", [(4, 64, 264, 136), (4, 32, 1800, 1544), (5, 50, 72, 264)])
+@pytest.mark.parametrize("pattern", ["first_zero", "last_zero", "one_left", "all_equal", "two_equal_runs"])
+def test_weight_patterns(dp, B, T, d, p, pattern):
+    # zero weights skip their samples (also at the ends of the batch); equal consecutive weights
+    # take the path that leaves the accumulator as it is
+    w = si.small_workload("wp", si.BF16, B, T, [(d, p)])
+    a, g = si.gen_layer(w, 0)
+    C = np.random.default_rng(3).uniform(0.05, 1.0, B).astype(np.float32)
+    if pattern == "first_zero":
+        C[0] = 0.0
+    elif pattern == "last_zero":
+        C[-1] = 0.0
+    elif pattern == "one_left":
+        C[:] = 0.0
+        C[B // 2] = 0.37
+    elif pattern == "all_equal":
+        C[:] = 0.61
+    else:
+        C[: B // 2] = 1.0
+        C[B // 2:] = 0.25
+    grad = torch.full((d, p), -2.0, dtype=torch.float32, device="cuda")
+    dp.dp_clipped_grad(dev(a), dev(g), dp.DP_BF16, B, T, d, p, dev(C), grad, 0)
+    G = o.clipped_grad(si.to_f64(a), si.to_f64(g), C.astype(np.float64))
+    assert frob(host(grad), G) <= 1e-5
+
+
 def test_bf16_unclipped_is_plain_product(dp):
     # C = 1: the standard gradient a^T g over all B*T rows.
     B, T, d, p = 3, 200, 264, 136
