@@ -550,3 +550,45 @@ def test_bias_joins_the_group_norm():
         assert res["C"][0, i] * math.sqrt(total) <= 1.0 + 1e-12
     assert res["flat"].size == 3 * 4 + 4
     np.testing.assert_allclose(res["flat"][12:], res["bias_grads"][0], rtol=1e-6)
+
+
+# ----------------------------------------------------------------------------
+# fixtures under tests/golden/
+# ----------------------------------------------------------------------------
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [line.split() for line in f if line.strip() and not line.startswith("#")]
+
+
+def test_philox_published_known_answers():
+    # The generator is pinned to the published algorithm by its authors' known-answer vectors.
+    rows = _rows("philox4x32_10_known_answers.txt")
+    assert len(rows) == 3
+    for row in rows:
+        words = [int(x, 16) for x in row]
+        got = o.philox4x32_10(*words[0:4], *words[4:6])
+        assert [int(x) for x in got] == words[6:10]
+
+
+def test_synthetic_inputs_lie_in_the_ranges_the_paper_prints():
+    # Loss-scaling table of section 3.4, row "DP w/o scaling".  Typical magnitudes (1st percentile
+    # to maximum of the absolute values) of the synthetic activations and output gradients must lie
+    # inside the printed ranges; Gram diagonals within a decade of theirs (the table is for one
+    # model, the stand-in layers are 768 to 3072 wide).
+    rng = {r[0]: (float(r[1]), float(r[2])) for r in _rows("loss_scaling_table_ranges.txt")}
+    w = si.WORKLOADS["cfg1"]
+    w = si.small_workload("ranges", w.dtype, 2, w.T, w.layers[:4], g_std=w.g_std, g_layer_scale=True)
+    for l in range(w.L):
+        a, g = (si.to_f64(x) for x in si.gen_layer(w, l))
+        for x, key in ((a, "activation"), (g, "output_grad")):
+            mag = np.abs(x[x != 0])
+            lo, hi = rng[key]
+            assert np.percentile(mag, 1) >= lo and mag.max() <= hi, (l, key)
+        for x, key in ((a, "gram_activation"), (g, "gram_output_grad")):
+            diag = np.einsum("itk,itk->it", x, x)
+            lo, hi = rng[key]
+            assert diag.min() >= lo / 10 and diag.max() <= hi * 10, (l, key, diag.min(), diag.max())
