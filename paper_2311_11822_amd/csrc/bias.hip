@@ -9,12 +9,12 @@ namespace dpbk {
 
 namespace {
 
-constexpr int kRowGroups = 8, kColThreads = 32;
+constexpr int kRowGroups = 16, kColThreads = 32;
 
 // One workgroup: sample blockIdx.y, a strip of 32 * VEC columns.  Thread (rg, ct) adds rows
-// rg, rg + 8, ... of its VEC columns; the 8 row groups are then added in order through LDS.
+// rg, rg + 16, ... of its VEC columns; the 16 row groups are then added in order through LDS.
 template <int DT>                       // dp_dtype of g
-__global__ void __launch_bounds__(kRowGroups* kColThreads)
+__global__ void __launch_bounds__(kRowGroups * kColThreads)
 bias_colsum_kernel(const void* __restrict__ g_all, int T, int p, float* __restrict__ colsum) {
   constexpr bool HALF = DT != DP_F32;   // 16-bit storage: 8 columns per thread
   constexpr int VEC = HALF ? 8 : 1;
@@ -28,8 +28,7 @@ bias_colsum_kernel(const void* __restrict__ g_all, int T, int p, float* __restri
   if (col < p) {
     if (HALF) {
       const uint16_t* g = static_cast<const uint16_t*>(g_all) + (size_t)i * T * p + col;
-      for (int t = rg; t < T; t += kRowGroups) {
-        const uint4 w = *reinterpret_cast<const uint4*>(g + (size_t)t * p);
+      auto add = [&](const uint4& w) {
         const uint32_t u[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -41,7 +40,18 @@ bias_colsum_kernel(const void* __restrict__ g_all, int T, int p, float* __restri
             acc[2 * q + 1] += (float)__builtin_bit_cast(_Float16, (uint16_t)(u[q] >> 16));
           }
         }
+      };
+      // four rows in flight per thread; they are added in row order, so the sum does not depend
+      // on the unrolling
+      int t = rg;
+      for (; t + 3 * kRowGroups < T; t += 4 * kRowGroups) {
+        uint4 w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[u] = *reinterpret_cast<const uint4*>(g + (size_t)(t + u * kRowGroups) * p);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) add(w[u]);
       }
+      for (; t < T; t += kRowGroups) add(*reinterpret_cast<const uint4*>(g + (size_t)t * p));
     } else {
       const float* g = static_cast<const float*>(g_all) + (size_t)i * T * p + col;
       for (int t = rg; t < T; t += kRowGroups) acc[0] += g[(size_t)t * p];
