@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--separate-noise", action="store_true",
                     help="add the noise in a pass of its own (dp_add_noise) instead of in the gradient "
                          "kernels' epilogue (dp_clipped_grad_noise_multi, the faster of the two)")
+    ap.add_argument("--clipping", default="all-layer", choices=["all-layer", "layer-wise"],
+                    help="all-layer: one clipping group (the metric's setting); layer-wise: one group per "
+                         "layer with thresholds R / sqrt(L), noise in a pass of its own")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
                     help="store a and g of a 16-bit workload in this type instead of the workload's own")
     args = ap.parse_args()
@@ -106,7 +109,10 @@ def main():
         layers.append((torch.from_numpy(view(a)).cuda(), torch.from_numpy(view(g)).cuda()))
     pipe = BkPipeline(layers)
     off, cnt = w.noise_range()
-    fused = not args.separate_noise
+    layerwise = args.clipping == "layer-wise"
+    fused = not args.separate_noise and not layerwise
+    if layerwise:
+        pipe.set_groups(list(range(w.L)), [w.R / w.L ** 0.5] * w.L)
 
     def step(ev=None):
         if ev:
@@ -114,16 +120,23 @@ def main():
         pipe.norms()
         if ev:
             ev[1].record()
-        pipe.clip(w.clip_mode, w.R, w.stability)
+        if layerwise:
+            pipe.clip_grouped(w.clip_mode, w.stability)
+        else:
+            pipe.clip(w.clip_mode, w.R, w.stability)
         if ev:
             ev[2].record()
-        if fused:
+        if layerwise:
+            pipe.grad_grouped()
+        elif fused:
             pipe.grad_noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
         else:
             pipe.grad()
         if ev:
             ev[3].record()
-        if not fused:
+        if layerwise:
+            pipe.noise_grouped(w.sigma, w.noise_seed, w.noise_step, off, cnt)
+        elif not fused:
             pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
         if ev:
             ev[4].record()
@@ -168,6 +181,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} T={w.T} L={w.L} layers, psi={w.psi}",
                    "clip": "automatic" if w.clip_mode == si.CLIP_AUTOMATIC else "standard",
+                   "clipping": args.clipping,
                    "R": w.R, "sigma": w.sigma, "noise_elements": cnt,
                    "noise": "in the gradient kernels' epilogue" if fused else "separate pass"},
         "tflops_nominal": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,

@@ -65,6 +65,28 @@ class BkPipeline:
     def noise(self, sigma, R, seed, step, offset, count, stream=None):
         dp.dp_add_noise(self.flat.data_ptr() + 4 * offset, offset, count, sigma, R, seed, step, stream)
 
+    # group-wise clipping (eq. (1) of the paper with M groups; layer-wise = one group per layer)
+    def set_groups(self, group_of_layer: Sequence[int], R: Sequence[float]):
+        """Layers must be listed group by group (group_of_layer non-decreasing)."""
+        M = len(R)
+        assert list(group_of_layer) == sorted(group_of_layer) and max(group_of_layer) < M
+        self.group_of_layer = list(group_of_layer)
+        self.group_begin = [sum(1 for x in group_of_layer if x < m) for m in range(M + 1)]
+        self.group_R = list(R)
+        self.C_groups = torch.zeros((M, self.B), dtype=torch.float32, device=self.device)
+        self.norm_groups = torch.zeros((M, self.B), dtype=torch.float32, device=self.device)
+
+    def clip_grouped(self, mode, stability=0.01, stream=None):
+        dp.dp_clip_factors_grouped(self.sqnorm, self.L, self.B, self.group_begin, self.group_R, mode, stability,
+                                   self.C_groups, self.norm_groups, stream)
+
+    def grad_grouped(self, accumulate=0, stream=None):
+        dp.dp_clipped_grad_grouped(self.desc, self.dt, self.B, self.C_groups, self.group_of_layer,
+                                   len(self.group_R), self.grad_ptrs, accumulate, stream)
+
+    def noise_grouped(self, sigma, seed, step, offset, count, stream=None):
+        self.noise(sigma, dp.dp_group_noise_threshold(self.group_R), seed, step, offset, count, stream)
+
     def step(self, mode, R, sigma, stability, seed, step, offset, count, stream=None, fused=True):
         self.norms(stream)
         self.clip(mode, R, stability, stream)

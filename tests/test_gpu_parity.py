@@ -531,6 +531,29 @@ def test_layerwise_clipping_with_biases(dp, dtype):
 # error paths: every refusal happens on the host, nothing is launched
 # ----------------------------------------------------------------------------
 
+def test_pipeline_layerwise_step(dp, Pipe):
+    # the sequence bench.py --clipping layer-wise times, against the oracle's group-wise path
+    dims = [(136, 264), (264, 136), (136, 136), (392, 24)]
+    w = si.small_workload("plw", si.BF16, 3, 96, dims)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    R = [0.02, 0.5, 0.1, 1e3]
+    sigma, seed, step = 0.4, 11, 2
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    pipe.set_groups([0, 1, 2, 3], R)
+    pipe.norms()
+    pipe.clip_grouped(dp.DP_CLIP_STANDARD, 0.01)
+    pipe.grad_grouped()
+    ref = o.private_gradient_grouped(l64, [0, 1, 2, 3], R, o.CLIP_STANDARD, 0.0, 0.01, seed, step, 0, 0)
+    assert rel(host(pipe.C_groups), ref["C"]) <= TOL_BF16_NORM
+    assert frob(host(pipe.flat), ref["flat"]) <= 1e-4
+    clean = host(pipe.flat).copy()
+    pipe.noise_grouped(sigma, seed, step, 0, pipe.psi)
+    z = (host(pipe.flat).astype(np.float64) - clean) / o.group_noise_std(sigma, R)
+    want = o.normals(seed, step, 0, pipe.psi)
+    assert np.all(np.abs(z - want) <= 2e-5 * np.maximum(1.0, np.abs(want)))
+
+
 # ----------------------------------------------------------------------------
 # gradient + noise in one pass (dp_clipped_grad_noise_multi)
 # ----------------------------------------------------------------------------
