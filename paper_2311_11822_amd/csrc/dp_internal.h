@@ -67,6 +67,20 @@ struct NoiseArgs {
 
 inline dp_status hip_status(hipError_t e) { return e == hipSuccess ? DP_OK : DP_ERR_HIP; }
 
+// Kernels that need more than 64 KiB of LDS must be told so once per device; `done` is the
+// caller's per-kernel table of devices already prepared.
+constexpr int kMaxDevices = 64;
+template <class K>
+dp_status allow_big_lds(K kernel, int bytes, bool (&done)[kMaxDevices]) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DP_ERR_HIP;
+  if (done[dev]) return DP_OK;
+  dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  if (st == DP_OK) done[dev] = true;
+  return st;
+}
+
 // --- launchers implemented in the .hip files (all validate nothing; callers did) ---
 dp_status launch_noise(float* grad, uint64_t global_offset, uint64_t count, float stddev,
                        uint64_t seed, uint64_t step, hipStream_t s);

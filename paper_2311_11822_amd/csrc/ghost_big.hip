@@ -375,15 +375,10 @@ bool ghost_big_supports(int T, int d, int p) {
 
 template <bool COMPACT, bool F16>
 dp_status launch_plan(const GroupArgs& ga, float* partials, hipStream_t s) {
-  static bool ready = false;
+  static bool ready[kMaxDevices] = {};
   auto kernel = ghost_big_kernel<COMPACT, F16>;
-  if (!ready) {
-    dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                  Plan<COMPACT>::LDS_BYTES));
-    if (st != DP_OK) return st;
-    ready = true;
-  }
+  dp_status st = allow_big_lds(kernel, Plan<COMPACT>::LDS_BYTES, ready);
+  if (st != DP_OK) return st;
   hipLaunchKernelGGL(kernel, dim3(ga.total_blocks), dim3(NT), Plan<COMPACT>::LDS_BYTES, s, ga, partials);
   return hip_status(hipGetLastError());
 }

@@ -671,17 +671,11 @@ dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, c
                                           hipStream_t s) {
   auto big = clipped_grad_big_kernel<F16, NOISE>;
   auto tail = clipped_grad_tail_kernel<F16, NOISE>;
-  static bool ready = false;
-  if (!ready) {
-    dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(big),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-    if (st != DP_OK) return st;
-    st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(tail),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)TailShape::LDS_BYTES));
-    if (st != DP_OK) return st;
-    ready = true;
-  }
+  static bool ready_big[kMaxDevices] = {}, ready_tail[kMaxDevices] = {};
+  dp_status st0 = allow_big_lds(big, LDS_BYTES, ready_big);
+  if (st0 != DP_OK) return st0;
+  st0 = allow_big_lds(tail, (int)TailShape::LDS_BYTES, ready_tail);
+  if (st0 != DP_OK) return st0;
   const int n = ga.total_blocks;
   int n_tail = n % kRound;
   if (n_tail > DP_TAIL_MAX) n_tail = 0;
