@@ -331,6 +331,30 @@ def test_multi_layer_stack_mixed_paths(dp, Pipe, dtype):
         assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, C)) <= 1e-4
 
 
+def test_standard_clipping_takes_both_branches(dp, Pipe):
+    # Output gradients small enough that some samples fall below R (C_i = 1) while others are
+    # clipped (C_i < 1): per-sample scales spread the norms around R.
+    dims = [(136, 264), (264, 136)]
+    B, T = 6, 96
+    w = si.small_workload("both", si.BF16, B, T, dims, g_std=1e-2)
+    layers = gen(w)
+    scale = np.array([1e-3, 3.0, 1e-2, 1.0, 1e-4, 10.0], dtype=np.float32)    # applied in fp32, rounded again
+    layers = [(a, si.f32_to_bf16_bits(si.bf16_bits_to_f32(g) * scale[:, None, None])) for a, g in layers]
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    pipe.norms()
+    pipe.clip(dp.DP_CLIP_STANDARD, 1.0)
+    pipe.grad()
+    sqn = np.stack([o.ghost_sqnorm(a, g) for a, g in l64])
+    C, norm = o.clip_factors(sqn, o.CLIP_STANDARD, 1.0, 0.01)
+    assert (C == 1.0).sum() >= 2 and (C < 1.0).sum() >= 2
+    got = host(pipe.C)
+    assert np.array_equal(got == 1.0, C == 1.0)
+    assert rel(got, C) <= TOL_BF16_NORM
+    for l, (a, g) in enumerate(l64):
+        assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, C)) <= 1e-4
+
+
 # ----------------------------------------------------------------------------
 # full-size workloads
 # ----------------------------------------------------------------------------
@@ -422,7 +446,28 @@ def test_cfg2_gpt2_large_full(dp, Pipe):
 
 
 def test_cfg4_wide_block_shard(dp, Pipe):
-    run_workload(dp, Pipe, "cfg4")
+    import dataclasses
+    pipe = run_workload(dp, Pipe, "cfg4")
+    # the shard of rank 2 of 8 crosses the boundary between the second and the third layer
+    w = dataclasses.replace(si.WORKLOADS["cfg4"], shard_rank=2)
+    off, cnt = w.noise_range()
+    edge = w.layer_offsets()[2]
+    assert off < edge < off + cnt
+    pipe.grad()
+    before = pipe.flat.clone()
+    pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+    std = w.sigma * w.R
+    for lo in (off, edge - 2048, off + cnt - 4096):
+        z = (host(pipe.flat[lo:lo + 4096]).astype(np.float64) - host(before[lo:lo + 4096])) / std
+        ref = o.normals(w.noise_seed, w.noise_step, lo, 4096)
+        assert np.all(np.abs(z - ref) <= 2e-5 * np.maximum(1.0, np.abs(ref)))
+    assert torch.equal(pipe.flat[:off], before[:off])
+    assert torch.equal(pipe.flat[off + cnt:], before[off + cnt:])
+    two_pass = pipe.flat.clone()
+    del before
+    pipe.flat.fill_(-3.0)
+    pipe.grad_noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+    assert torch.equal(pipe.flat, two_pass)
 
 
 # ----------------------------------------------------------------------------
