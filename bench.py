@@ -154,6 +154,8 @@ def main():
     stage = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(4)] for e in events])   # ms
     ms_norm, ms_clip, ms_grad, ms_noise = stage.mean(axis=0)
     ms_step = elapsed * 1e3 / args.steps
+    per_step = stage.sum(axis=1)               # event time of each step, first norm kernel to last kernel
+    props = torch.cuda.get_device_properties(0)
     norm_flops, grad_flops = workload_flops(w)
     grad_launches = -(-w.L // 48) if w.dtype != si.F32 else w.L
     grad_tflops = grad_flops / (ms_grad * 1e-3) / 1e12
@@ -187,6 +189,11 @@ def main():
         "tflops_nominal": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,
         "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
+        "ms_per_step_events": {"median": float(np.median(per_step)), "min": float(per_step.min())},
+        "seeds": {"data": w.data_seed, "noise": w.noise_seed, "noise_step": w.noise_step},
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "clock_mhz": (getattr(props, "clock_rate", 0) or 0) / 1e3 or None,
+                   "peak_bf16_tflops_used": PEAK_BF16_FLOPS / 1e12, "peak_hbm_gbps_used": PEAK_HBM_BYTES / 1e9},
         "noise_gbps": None if fused else 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
         "roofline": {"kernel": "clipped_grad_big_kernel (+ clipped_grad_tail_kernel)" if w.dtype != si.F32
                      else "clipped_grad_f32_kernel",
