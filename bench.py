@@ -39,6 +39,23 @@ def workload_flops(w):
     return norm, grad
 
 
+def ghost_flops_executed(w):
+    """Flops the large-tile ghost-norm kernel issues (it uses the Gram matrices' symmetry): per
+    sample and tile row I of 256 tokens, one 128 x 128 diagonal tile and 256 x 128 tiles for the
+    column blocks J > 2I; each over d + p.  Layers on other kernels count with the nominal figure."""
+    total = 0.0
+    for d, p in w.layers:
+        T = w.T
+        if 2 * T * T > d * p or T < 96 or d % 64 or p % 64:
+            total += 2.0 * w.B * T * T * (d + p) if 2 * T * T <= d * p else 2.0 * w.B * T * d * p
+            continue
+        nj, ni = -(-T // 128), -(-T // 256)
+        for I in range(ni):
+            full = nj - 2 * I - 1
+            total += w.B * (2.0 * 128 * 128 + full * 2.0 * 256 * 128) * (d + p)
+    return total
+
+
 def cpu_baseline(w, budget_layers):
     """The oracle as it stands on the host cores, on the first `budget_layers` layers of the
     workload (whole path on them: norms, clip factors, gradient, noise on their elements)."""
@@ -189,6 +206,8 @@ def main():
         "tflops_nominal": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,
         "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
+        "norm_stage": {"tflops_nominal": norm_flops / (ms_norm * 1e-3) / 1e12,
+                       "tflops_executed": ghost_flops_executed(w) / (ms_norm * 1e-3) / 1e12},
         "ms_per_step_events": {"median": float(np.median(per_step)), "min": float(per_step.min())},
         "seeds": {"data": w.data_seed, "noise": w.noise_seed, "noise_step": w.noise_step},
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
