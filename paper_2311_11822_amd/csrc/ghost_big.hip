@@ -226,10 +226,10 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   // per wave); the vmcnt immediates and the interleave must be constants, hence separate
   // instantiations of the loop.
   //
-  // General plan, iteration kb: a wave waits for its own loads of block kb, meets the others at
-  // one barrier (block kb is in LDS, block kb-1 is no longer read), fetches the first fragments,
-  // then runs the MFMAs with the loads of block kb+2 (into the stage of block kb-1) and the
-  // fragment reads of the next k-step in their shadow.  A load has two iterations to land.
+  // General plan: a wave waits for its own loads of block m, meets the others at one barrier
+  // (block m is in LDS, block m-1 has been read), and runs the MFMAs with the loads of block
+  // m+2 (into the stage of block m-1) and the fragment reads of the next k-step in their shadow.
+  // A load has two iterations to land.
   auto run = [&](auto inside_tag, auto mi_tag) {
     constexpr bool ins = decltype(inside_tag)::value;
     constexpr int MI = decltype(mi_tag)::value;
@@ -250,32 +250,66 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
       advance();
     }
     int c_stage = 0;
-    auto block = [&](f32x16 (&acc)[4][2]) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * PER) : "memory");
-      __builtin_amdgcn_s_barrier();
+    // One k-step: 2 MI MFMAs on fragment buffer KS & 1, with the fragment reads of the following
+    // k-step (k-step r_ks of the block in r_stage) and the loads of window position POS in
+    // their shadow.
+    auto kstep = [&](f32x16 (&acc)[4][2], auto ks_tag, auto pos_tag, bool fetch, int r_stage, int r_ks) {
+      constexpr int KS = decltype(ks_tag)::value, POS = decltype(pos_tag)::value;
+      constexpr int cb = KS & 1, nb = cb ^ 1;
 #pragma unroll
-      for (int it = 0; it < 2 + MI; ++it) read_frag(0, it, c_stage, 0);
-      DP_PIN();
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const int cb = ks & 1, nb = cb ^ 1;
-#pragma unroll
-        for (int n = 0; n < 2 * MI; ++n) {
-          const int i = n >> 1, j = n & 1;
-          acc[i][j] = mfma16<F16>(fa[cb][i], fb[cb][j], acc[i][j]);
-          DP_PIN();
-          if (ks < 3 && n < 2 + MI) read_frag(nb, n, c_stage, ks + 1);
+      for (int n = 0; n < 2 * MI; ++n) {
+        const int i = n >> 1, j = n & 1;
+        acc[i][j] = mfma16<F16>(fa[cb][i], fb[cb][j], acc[i][j]);
+        DP_PIN();
+        if (fetch && n < 2 + MI) read_frag(nb, n, r_stage, r_ks);
+        if (POS >= 0) {
 #pragma unroll
           for (int x = 0; x < PER_KS; ++x)
-            if (n == load_slot(MI, PER_KS, x)) issue_nth(ks * PER_KS + x);
-          DP_PIN();
+            if (n == load_slot(MI, PER_KS, x)) issue_nth((POS < 0 ? 0 : POS) * PER_KS + x);
         }
+        DP_PIN();
       }
-      advance();
-      c_stage = c_stage + 1 == NSTAGE ? 0 : c_stage + 1;
     };
-    for (int kb = 0; kb < nka; ++kb) block(sa);
-    for (int kb = 0; kb < nkg; ++kb) block(sg);
+    using K0 = std::integral_constant<int, 0>;
+    using K1 = std::integral_constant<int, 1>;
+    using K2 = std::integral_constant<int, 2>;
+    using K3 = std::integral_constant<int, 3>;
+    using NoLoads = std::integral_constant<int, -1>;
+    // The barrier that certifies block m sits before the last k-step of block m-1, whose
+    // fragments are in registers by then, so the first fragments of block m are read during
+    // those MFMAs and no LDS latency is exposed at the block boundary.  The loads of block m+2
+    // (into the stage of block m-1, which nobody reads any more) follow the barrier, spread over
+    // that k-step and the first three of block m.
+    // first block: its first fragments are the one exposed LDS latency of the tile
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * PER) : "memory");
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int it = 0; it < 2 + MI; ++it) read_frag(0, it, 0, 0);
+#pragma unroll
+    for (int x = 0; x < PER_KS; ++x) issue_nth(x);              // window position 0 has no MFMAs yet
+    DP_PIN();
+    kstep(sa, K0{}, K1{}, true, 0, 1);
+    kstep(sa, K1{}, K2{}, true, 0, 2);
+    kstep(sa, K2{}, K3{}, true, 0, 3);
+    advance();
+    auto iter = [&](f32x16 (&acc_old)[4][2], f32x16 (&acc_new)[4][2]) {
+      const int n_stage = c_stage + 1 == NSTAGE ? 0 : c_stage + 1;
+      // own loads of block m landed; own fragment reads of block m-1 returned (the loads that
+      // follow the barrier overwrite that block's stage)
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NSTAGE - 2) * PER) : "memory");
+      __builtin_amdgcn_s_barrier();
+      DP_PIN();
+      kstep(acc_old, K3{}, K0{}, true, n_stage, 0);
+      kstep(acc_new, K0{}, K1{}, true, n_stage, 1);
+      kstep(acc_new, K1{}, K2{}, true, n_stage, 2);
+      kstep(acc_new, K2{}, K3{}, true, n_stage, 3);
+      advance();
+      c_stage = n_stage;
+    };
+    for (int m = 1; m < nka; ++m) iter(sa, sa);
+    iter(sa, sg);
+    for (int m = nka + 1; m < nblocks; ++m) iter(sg, sg);
+    kstep(sg, K3{}, NoLoads{}, false, 0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
   // Compact plan, iteration kb: wait for own loads of block kb+1, barrier (block kb+1 in LDS,
