@@ -576,6 +576,28 @@ def test_layerwise_clipping_with_biases(dp, dtype):
 # error paths: every refusal happens on the host, nothing is launched
 # ----------------------------------------------------------------------------
 
+def test_layerwise_normalising_variant(dp, Pipe):
+    # Appendix on the hook-free implementation: per layer, a_i^T g_i divided by its own norm,
+    # i.e. layer-wise automatic clipping with R = 1 and no stability constant.
+    dims = [(136, 264), (264, 136), (72, 24)]
+    w = si.small_workload("nv", si.BF16, 4, 96, dims)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    pipe.set_groups([0, 1, 2], [1.0, 1.0, 1.0])
+    pipe.norms()
+    pipe.clip_grouped(dp.DP_CLIP_AUTOMATIC, 0.0)
+    pipe.grad_grouped()
+    for l, (a, g) in enumerate(l64):
+        want = np.zeros(dims[l])
+        for i in range(w.B):
+            Gi = a[i].T @ g[i]
+            want += Gi / np.linalg.norm(Gi)             # every sample enters with unit norm
+        assert frob(host(pipe.grads[l]), want) <= 5e-3  # bf16-path norms: 2e-3 on each weight
+    ref = o.private_gradient_grouped(l64, [0, 1, 2], [1.0] * 3, o.CLIP_AUTOMATIC, 0.0, 0.0, 1, 0, 0, 0)
+    assert rel(host(pipe.C_groups), ref["C"]) <= TOL_BF16_NORM
+
+
 def test_pipeline_layerwise_step(dp, Pipe):
     # the sequence bench.py --clipping layer-wise times, against the oracle's group-wise path
     dims = [(136, 264), (264, 136), (136, 136), (392, 24)]
