@@ -69,3 +69,38 @@ def test_validation_refuses_before_any_launch(dp):
     assert lib.dp_philox_blocks(None, 0, 4, 0, 0, None) == INV
     with pytest.raises(dp.DpError):
         dp.dp_clip_factors(fake, 1, 1, 5, 1.0, 0.01, fake, stream=0)
+
+
+def test_validation_of_the_later_entry_points(dp):
+    import ctypes as C
+    lib, INV = dp.lib, dp.DP_ERR_INVALID_ARG
+    fake = 0x1000                     # never dereferenced: every call below fails validation
+    arr = dp.layer_array([(fake, fake, 8, 8, 8, 0)])
+    gp = (C.c_void_p * 1)(fake)
+    offs = (C.c_uint64 * 1)(0)
+    # fp16 is a storage type like bf16: rows must be multiples of 16 bytes
+    assert dp.dp_norm_workspace_bytes(0, dp.DP_F16, 4, 256, 768, 768) == dp.dp_norm_workspace_bytes(0, dp.DP_BF16, 4, 256, 768, 768)
+    assert dp.dp_norm_workspace_bytes(0, dp.DP_F16, 1, 256, 12, 8) == 0
+    assert dp.dp_norm_workspace_bytes(0, 3, 4, 256, 768, 768) == 0                   # unknown dtype
+    # gradients with noise
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, fake, gp, None, 0, 0, 16, 1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, fake, gp, offs, 0, 0, 16, float("nan"), 1.0, 0, 0, None) == INV
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, fake, gp, offs, 0, 0, 16, 1.0, 0.0, 0, 0, None) == INV
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 1, fake, gp, offs, 0, 2 ** 64 - 1, 2, 1.0, 1.0, 0, 0, None) == INV
+    assert lib.dp_clipped_grad_noise_multi(arr, 1, 1, 0, fake, gp, offs, 0, 0, 16, 1.0, 1.0, 0, 0, None) == INV   # B = 0
+    # group-wise clipping
+    begin, R = (C.c_int32 * 3)(0, 1, 2), (C.c_float * 2)(1.0, 1.0)
+    assert lib.dp_clip_factors_grouped(fake, 2, 4, begin, 2, R, 0, 0.01, None, None, None) == INV
+    assert lib.dp_clip_factors_grouped(fake, 2, 4, None, 2, R, 0, 0.01, fake, None, None) == INV
+    bad_begin = (C.c_int32 * 3)(0, 2, 1)                                            # not monotone
+    assert lib.dp_clip_factors_grouped(fake, 2, 4, bad_begin, 2, R, 0, 0.01, fake, None, None) == INV
+    bad_R = (C.c_float * 2)(1.0, -1.0)
+    assert lib.dp_clip_factors_grouped(fake, 2, 4, begin, 2, bad_R, 0, 0.01, fake, None, None) == INV
+    gol = (C.c_int32 * 1)(3)                                                         # group out of range
+    assert lib.dp_clipped_grad_grouped(arr, 1, 1, 1, fake, gol, 2, gp, 0, None) == INV
+    assert dp.dp_group_noise_threshold([3.0, 4.0]) == 5.0
+    # bias
+    assert lib.dp_bias_norm(None, 1, 1, 8, 8, fake, fake, None) == INV
+    assert lib.dp_bias_norm(fake, 1, 1, 8, 12, fake, fake, None) == INV             # 16-bit row not 16 B
+    assert lib.dp_clipped_bias_grad(fake, 1, 8, None, fake, 0, None) == INV
+    assert lib.dp_clipped_bias_grad(fake, 1, 8, fake, fake, 2, None) == INV
