@@ -103,11 +103,7 @@ struct GramTile {
   }
 };
 
-__device__ __forceinline__ int find_layer_g(const GroupArgs& ga, int block) {
-  int l = 0;
-  while (l + 1 < ga.n_layers && block >= ga.layer[l + 1].tile_begin) ++l;
-  return l;
-}
+__device__ __forceinline__ int find_layer_g(const GroupArgs& ga, int block) { return layer_of(ga, block); }
 
 template <class S, bool F16>
 __global__ void __launch_bounds__(S::NT)

@@ -109,8 +109,7 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
       logical = base + (xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx);
     }
   }
-  int l = 0;
-  while (l + 1 < ga.n_layers && logical >= ga.layer[l + 1].tile_begin) ++l;
+  const int l = layer_of(ga, logical);
   const GroupLayer& ly = ga.layer[l];
   const int local = logical - ly.tile_begin;
   const int sample = local / ly.tiles_per_sample;

@@ -90,8 +90,7 @@ struct Frag {
 // XCD then pull 12 operand panels per 32 tiles through that XCD's L2, and the 8 XCDs 32 panels
 // per 256 tiles through the memory-side cache.
 __device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& layer, int& m0, int& n0) {
-  int l = 0;
-  while (l + 1 < ga.n_layers && t >= ga.layer[l + 1].tile_begin) ++l;
+  const int l = layer_of(ga, t);
   layer = l;
   const GroupLayer& ly = ga.layer[l];
   int rem = t - ly.tile_begin;

@@ -20,11 +20,7 @@ namespace dpbk {
 
 namespace {
 
-__device__ __forceinline__ int find_layer(const GroupArgs& ga, int block) {
-  int l = 0;
-  while (l + 1 < ga.n_layers && block >= ga.layer[l + 1].tile_begin) ++l;
-  return l;
-}
+__device__ __forceinline__ int find_layer(const GroupArgs& ga, int block) { return layer_of(ga, block); }
 
 // ---------------------------------------------------------------------------------
 // Clip-weighted gradient, grouped over layers.
