@@ -299,6 +299,21 @@ def test_weight_patterns(dp, B, T, d, p, pattern):
     assert frob(host(grad), G) <= 1e-5
 
 
+@pytest.mark.parametrize("B,T,d,p", [(3, 96, 392, 520), (2, 32, 4360, 3848), (3, 50, 72, 264)])
+def test_gradient_is_reproducible_bit_for_bit(dp, B, T, d, p):
+    # no atomics and a fixed summation order in every gradient kernel: two runs give the same bits
+    w = si.small_workload("det", si.BF16, B, T, [(d, p)])
+    a, g = si.gen_layer(w, 0)
+    ad, gd = dev(a), dev(g)
+    Cd = dev(np.random.default_rng(9).uniform(0.1, 1.0, B).astype(np.float32))
+    runs = []
+    for _ in range(2):
+        grad = torch.zeros((d, p), dtype=torch.float32, device="cuda")
+        dp.dp_clipped_grad(ad, gd, dp.DP_BF16, B, T, d, p, Cd, grad, 0)
+        runs.append(grad)
+    assert torch.equal(runs[0], runs[1])
+
+
 def test_bf16_unclipped_is_plain_product(dp):
     # C = 1: the standard gradient a^T g over all B*T rows.
     B, T, d, p = 3, 200, 264, 136
