@@ -5,14 +5,19 @@ One step = the whole hot path over one synthetic micro-batch: per-layer per-samp
 (ghost or instantiated by the path rule) -> clip factors -> clip-weighted gradients of every
 layer -> Gaussian noise on the rank's shard.  Inputs are resident in HBM before timing.
 
-Prints ONE JSON line: samples/s, ms per step, per-stage times, the roofline of the dominant
-kernel (the clip-weighted gradient GEMM, measured with events around its launches inside the
-timed loop) and the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line.  The top-level figures are for the workload of record, cfg4 (one GPU's share
+of a 12288-wide block at its real shape, the matrix-core-bound configuration): samples/s, ms per
+step, per-stage times, the roofline of the dominant kernel (the clip-weighted gradient GEMM,
+timed with events around its launches inside the timed loop) and the CPU oracle timed on a bounded
+sample of the same workload.  `per_config` holds the same measurements for cfg1, cfg2 and cfg3
+taken in the same process, and `noise_pass` the separate noise pass (dp_add_noise) on cfg4's
+shard and on cfg2's whole gradient, as bytes moved per second against the HBM peak.
 """
 from __future__ import annotations
 
 import argparse
 import dataclasses
+import gc
 import json
 import os
 import sys
@@ -27,9 +32,12 @@ import synth_inputs as si  # noqa: E402
 
 PEAK_BF16_FLOPS = 2.5e15       # MI355X dense bf16 MFMA
 PEAK_HBM_BYTES = 8.0e12
+HEADLINE = "cfg4"
 
 
 def workload_flops(w):
+    """(norm, gradient) flops by the paper's formulas: ghost norm 2 B T^2 (d + p), instantiated
+    norm and weighted gradient 2 B T d p each."""
     BT = w.B * w.T
     grad = sum(2.0 * BT * d * p for d, p in w.layers)
     norm = 0.0
@@ -56,23 +64,29 @@ def ghost_flops_executed(w):
     return total
 
 
-def cpu_baseline(w, budget_layers):
-    """The oracle as it stands on the host cores, on the first `budget_layers` layers of the
-    workload (whole path on them: norms, clip factors, gradient, noise on their elements)."""
+def cpu_baseline(w, layer_ids, n_samples):
+    """The oracle as it stands on the host cores, on a bounded sample of the workload: the whole
+    path (norms, clip factors, gradient, noise on the same fraction of the elements) on the listed
+    layers and the first n_samples samples; the result is scaled to the workload by the flop ratio."""
     from oracle import bk_oracle as o
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = len(os.sched_getaffinity(0))
-    sub = si.Workload(**{**w.__dict__, "layers": w.layers[:budget_layers], "shard_count": 1, "shard_rank": 0})
-    layers = [tuple(si.to_f64(x) for x in si.gen_layer(sub, l)) for l in range(sub.L)]
+    full = dataclasses.replace(w, layers=tuple(w.layers[l] for l in layer_ids))
+    sub = dataclasses.replace(full, B=n_samples)
+    layers = []
+    for l in range(full.L):
+        a, g = si.gen_layer(full, l)
+        layers.append((si.to_f64(a[:n_samples]), si.to_f64(g[:n_samples])))
+    off, cnt = sub.noise_range()
     # repeated until about 10 s of CPU work have been timed (at most 4 passes); dt = mean pass
     reps, total = 0, 0.0
     while reps < 4 and total < 10.0:
         t0 = time.perf_counter()
         o.private_gradient(layers, sub.clip_mode, sub.R, sub.sigma, sub.stability, sub.noise_seed,
-                           sub.noise_step, 0, sub.psi)
+                           sub.noise_step, off, cnt)
         total += time.perf_counter() - t0
         reps += 1
     dt = total / reps
@@ -81,49 +95,29 @@ def cpu_baseline(w, budget_layers):
     scale = (n_all + g_all) / (n_sub + g_sub)
     return {
         "value": w.B / (dt * scale), "unit": "samples/s", "cores": cores, "kind": "oracle",
-        "sample": f"whole path on the first {budget_layers} of {w.L} layers ({reps} passes, {dt:.2f} s each, float64 numpy), "
-                  f"scaled by the flop ratio {scale:.2f}",
+        "sample": f"whole path on layer(s) {list(layer_ids)} of {w.L}, {n_samples} of {w.B} samples, noise on "
+                  f"{cnt} elements ({reps} passes, {dt:.2f} s each, float64 numpy); extrapolated to the "
+                  f"workload by the flop ratio {scale:.2f}",
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg1", choices=sorted(si.WORKLOADS))
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--separate-noise", action="store_true",
-                    help="add the noise in a pass of its own (dp_add_noise) instead of in the gradient "
-                         "kernels' epilogue (dp_clipped_grad_noise_multi, the faster of the two)")
-    ap.add_argument("--clipping", default="all-layer", choices=["all-layer", "layer-wise"],
-                    help="all-layer: one clipping group (the metric's setting); layer-wise: one group per "
-                         "layer with thresholds R / sqrt(L), noise in a pass of its own")
-    ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
-                    help="store a and g of a 16-bit workload in this type instead of the workload's own")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+# oracle sample per workload: (layer indices, samples), sized for 5-15 s per pass
+BASELINE_SAMPLE = {"cfg0": ((0,), 4), "cfg1": (tuple(range(48)), 16), "cfg2": (tuple(range(8)), 8),
+                   "cfg3": ((0, 1, 2, 3), 2), "cfg4": ((1,), 2)}
 
-    import torch
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    from paper_2311_11822_amd import binding as dp
-    from paper_2311_11822_amd.pipeline import BkPipeline
 
-    w = si.WORKLOADS[args.workload]
+def measure(name, args, torch, BkPipeline, noise_pass=False):
+    """Times `args.steps` steps of workload `name` after `args.warmup` untimed ones; returns the
+    measurements as a dict.  Device memory is released before returning."""
+    w = si.WORKLOADS[name]
     if args.dtype and w.dtype != si.F32:
         w = dataclasses.replace(w, dtype={"bf16": si.BF16, "f16": si.F16}[args.dtype])
-    baseline = None
-    if not args.no_cpu_baseline:
-        budget = {"cfg0": 1, "cfg1": 48, "cfg2": 16, "cfg3": 4, "cfg4": 1}[w.name]
-        baseline = cpu_baseline(w, budget)
-
     layers = []
     for l in range(w.L):
         a, g = si.gen_layer(w, l)
         view = (lambda x: x.view(np.int16)) if w.dtype == si.BF16 else (lambda x: x)
         layers.append((torch.from_numpy(view(a)).cuda(), torch.from_numpy(view(g)).cuda()))
+        del a, g
     pipe = BkPipeline(layers)
     off, cnt = w.noise_range()
     layerwise = args.clipping == "layer-wise"
@@ -172,15 +166,100 @@ def main():
     ms_norm, ms_clip, ms_grad, ms_noise = stage.mean(axis=0)
     ms_step = elapsed * 1e3 / args.steps
     per_step = stage.sum(axis=1)               # event time of each step, first norm kernel to last kernel
-    props = torch.cuda.get_device_properties(0)
     norm_flops, grad_flops = workload_flops(w)
+    norm_exec = ghost_flops_executed(w)
     grad_launches = -(-w.L // 48) if w.dtype != si.F32 else w.L
-    grad_tflops = grad_flops / (ms_grad * 1e-3) / 1e12
-    # The gradient of one group of up to 48 layers is one launch of clipped_grad_big_kernel plus,
-    # when the last round of tiles is nearly empty, one of clipped_grad_tail_kernel for those
-    # tiles; "launch" below means that pair, timed together by the events around the stage.
-    # HBM-side bytes per launch from the committed rocprofv3 counter runs
-    # (profiles/<workload>_all_kernels.md); null when this workload has not been profiled.
+    res = {
+        "workload": f"{w.name}: B={w.B} T={w.T} L={w.L} layers, psi={w.psi}",
+        "dtype": w.dtype,
+        "clip": "automatic" if w.clip_mode == si.CLIP_AUTOMATIC else "standard",
+        "noise": "in the gradient kernels' epilogue" if fused else "separate pass",
+        "noise_elements": cnt,
+        "ms_per_step": ms_step,
+        "samples_per_s": w.B / (ms_step * 1e-3),
+        "ms_per_step_events": {"median": float(np.median(per_step)), "min": float(per_step.min())},
+        "stage_ms": {"norms": float(ms_norm), "clip": float(ms_clip), "grad": float(ms_grad), "noise": float(ms_noise)},
+        # executed = what the kernels issue (the ghost-norm kernel skips the lower triangle of the
+        # symmetric Gram matrices); model = the paper's operation counts (complexity table, section 3)
+        "tflops_executed": (norm_exec + grad_flops) / (ms_step * 1e-3) / 1e12,
+        "pct_bf16_peak": 100.0 * (norm_exec + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
+        "tflops_model": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,
+        "pct_bf16_peak_model_flops": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
+        "norm_stage": {"tflops_model": norm_flops / (ms_norm * 1e-3) / 1e12,
+                       "tflops_executed": norm_exec / (ms_norm * 1e-3) / 1e12},
+        "grad_stage": {"tflops": grad_flops / (ms_grad * 1e-3) / 1e12,
+                       "frac_bf16_peak": grad_flops / (ms_grad * 1e-3) / PEAK_BF16_FLOPS,
+                       "launches_per_step": grad_launches,
+                       "flops_per_step": grad_flops},
+    }
+    if noise_pass:
+        # the separate noise pass on this workload's shard: 4 bytes read + 4 written per element
+        for _ in range(2):
+            pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for k in range(args.steps):
+            pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step + 1 + k, off, cnt)
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        ms = np.array([ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)])
+        gbps = 8.0 * cnt / (ms.mean() * 1e-3) / 1e9
+        res["noise_pass"] = {"kernel": "noise_bulk_kernel", "elements": cnt, "bytes": 8 * cnt,
+                             "ms": float(ms.mean()), "ms_min": float(ms.min()),
+                             "gbps": gbps, "frac_hbm_peak": gbps * 1e9 / PEAK_HBM_BYTES}
+    del pipe, layers
+    gc.collect()
+    torch.cuda.empty_cache()
+    return w, res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=HEADLINE, choices=sorted(si.WORKLOADS),
+                    help="workload of the top-level figures (default: cfg4, the metric's configuration)")
+    ap.add_argument("--only", action="store_true",
+                    help="measure the --workload alone: no per_config block, no cfg2 noise pass")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-noise", action="store_true",
+                    help="add the noise in a pass of its own (dp_add_noise) instead of in the gradient "
+                         "kernels' epilogue (dp_clipped_grad_noise_multi, the faster of the two)")
+    ap.add_argument("--clipping", default="all-layer", choices=["all-layer", "layer-wise"],
+                    help="all-layer: one clipping group (the metric's setting); layer-wise: one group per "
+                         "layer with thresholds R / sqrt(L), noise in a pass of its own")
+    ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
+                    help="store a and g of a 16-bit workload in this type instead of the workload's own")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2311_11822_amd.pipeline import BkPipeline
+
+    baseline = None
+    if not args.no_cpu_baseline:
+        ids, n = BASELINE_SAMPLE[args.workload]
+        baseline = cpu_baseline(si.WORKLOADS[args.workload], ids, n)
+
+    w, head = measure(args.workload, args, torch, BkPipeline, noise_pass=True)
+    per_config, noise_pass = {}, {f"{w.name}_shard": head.pop("noise_pass")}
+    if not args.only:
+        for name in ("cfg1", "cfg2", "cfg3"):
+            if name == args.workload:
+                continue
+            _, r = measure(name, args, torch, BkPipeline, noise_pass=(name == "cfg2"))
+            if "noise_pass" in r:
+                noise_pass[f"{name}_full"] = r.pop("noise_pass")
+            per_config[name] = r
+
+    # Bytes per launch that missed the XCDs' L2 caches (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled
+    # by what the same counters read for a device copy of known size): profiles/hbm_traffic.json,
+    # written from the committed counter runs; null when this workload has not been profiled.
     traffic = None
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
@@ -189,40 +268,48 @@ def main():
                       for k in ("clipped_grad_big_kernel", "clipped_grad_tail_kernel") if k in per)
     except (OSError, KeyError, ValueError):
         pass
+    props = torch.cuda.get_device_properties(0)
+    gs = head["grad_stage"]
+    ms_grad = head["stage_ms"]["grad"]
     out = {
         "metric": "clipped-gradient samples/sec",
-        "value": w.B / (ms_step * 1e-3),
+        "value": head["samples_per_s"],
         "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype,
+        "dtype": head["dtype"],
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: B={w.B} T={w.T} L={w.L} layers, psi={w.psi}",
-                   "clip": "automatic" if w.clip_mode == si.CLIP_AUTOMATIC else "standard",
-                   "clipping": args.clipping,
-                   "R": w.R, "sigma": w.sigma, "noise_elements": cnt,
-                   "noise": "in the gradient kernels' epilogue" if fused else "separate pass"},
-        "tflops_nominal": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,
-        "pct_bf16_peak": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
-        "stage_ms": {"norms": ms_norm, "clip": ms_clip, "grad": ms_grad, "noise": ms_noise},
-        "norm_stage": {"tflops_nominal": norm_flops / (ms_norm * 1e-3) / 1e12,
-                       "tflops_executed": ghost_flops_executed(w) / (ms_norm * 1e-3) / 1e12},
-        "ms_per_step_events": {"median": float(np.median(per_step)), "min": float(per_step.min())},
+        "config": {"workload": head["workload"], "clip": head["clip"], "clipping": args.clipping,
+                   "R": w.R, "sigma": w.sigma, "noise_elements": head["noise_elements"], "noise": head["noise"]},
+        "tflops_executed": head["tflops_executed"],
+        "pct_bf16_peak": head["pct_bf16_peak"],
+        "tflops_model": head["tflops_model"],
+        "pct_bf16_peak_model_flops": head["pct_bf16_peak_model_flops"],
+        "stage_ms": head["stage_ms"],
+        "norm_stage": head["norm_stage"],
+        "ms_per_step_events": head["ms_per_step_events"],
         "seeds": {"data": w.data_seed, "noise": w.noise_seed, "noise_step": w.noise_step},
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "clock_mhz": (getattr(props, "clock_rate", 0) or 0) / 1e3 or None,
                    "peak_bf16_tflops_used": PEAK_BF16_FLOPS / 1e12, "peak_hbm_gbps_used": PEAK_HBM_BYTES / 1e9},
-        "noise_gbps": None if fused else 8.0 * cnt / (ms_noise * 1e-3) / 1e9,
+        # separate noise pass (dp_add_noise) on this workload's shard; the timed step above adds
+        # the noise in the gradient kernels' epilogue unless --separate-noise
+        "noise_gbps": noise_pass[f"{w.name}_shard"]["gbps"],
+        "noise_pass": noise_pass,
+        # The gradient of one group of up to 48 layers is one launch of clipped_grad_big_kernel
+        # plus, when the last round of tiles is nearly empty, one of clipped_grad_tail_kernel for
+        # those tiles; "launch" below means that pair, timed together by the events around the stage.
         "roofline": {"kernel": "clipped_grad_big_kernel (+ clipped_grad_tail_kernel)" if w.dtype != si.F32
                      else "clipped_grad_f32_kernel",
                      "bound": "mfma",
-                     "achieved": grad_tflops, "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
-                     "frac": grad_tflops * 1e12 / PEAK_BF16_FLOPS,
-                     "launches_per_step": grad_launches,
-                     "avg_launch_ms": ms_grad / grad_launches,
-                     "algorithmic_flops_per_launch": grad_flops / grad_launches,
+                     "achieved": gs["tflops"], "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
+                     "frac": gs["frac_bf16_peak"],
+                     "launches_per_step": gs["launches_per_step"],
+                     "avg_launch_ms": ms_grad / gs["launches_per_step"],
+                     "algorithmic_flops_per_launch": gs["flops_per_step"] / gs["launches_per_step"],
                      "traffic": traffic},
+        "per_config": per_config,
         "cpu_baseline": baseline,
     }
     print(json.dumps(out))

@@ -18,15 +18,25 @@
  *    never dereferences a device pointer on the host.
  *  - Tensors are dense and row-major with the last index contiguous.  bf16
  *    tensors must be 16-byte aligned, fp32 tensors 16-byte aligned.
- *  - The caller owns every buffer.  The library allocates no device memory,
- *    keeps no mutable global state and never synchronises: work is enqueued on
- *    `stream` (a hipStream_t passed as void*; NULL is the default stream) and the
- *    call returns at once.  Calls on one stream execute in order.
- *  - Results are deterministic: no floating-point atomics are used, so the same
- *    inputs give the same bits on every run.
+ *  - The caller owns every buffer.  The library allocates no device memory and
+ *    never synchronises: work is enqueued on `stream` (a hipStream_t passed as
+ *    void*; NULL is the default stream) and the call returns at once.  Calls on
+ *    one stream execute in order.  The only state the library keeps between calls
+ *    is a per-device table of flags recording which kernels have been allowed
+ *    their large LDS allocation (set once, atomically; calls from several host
+ *    threads are safe).
+ *  - Results are deterministic: no floating-point atomics are used and every sum
+ *    is taken in a fixed order, so the same inputs give the same bits on every run.
  *  - Errors are return codes.  Arguments are validated on the host before
- *    anything is launched (DP_ERR_INVALID_ARG, DP_ERR_WORKSPACE); a failed
- *    launch gives DP_ERR_HIP.  On any error nothing has been enqueued.
+ *    anything is launched: a validation error (DP_ERR_INVALID_ARG,
+ *    DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE) means nothing has been enqueued.  A
+ *    launch the runtime refuses gives DP_ERR_HIP; the multi-layer calls consist of
+ *    several launches, so earlier ones may already be queued then.
+ *  - DP_F32 layers run on the vector ALUs, one workgroup per sample in the norm
+ *    kernels: they are meant for layers of a few thousand elements.  A norm that
+ *    needs more than 2^28 multiply-adds per sample (T^2 (d_in + d_out) / 2 for the
+ *    ghost norm, T d_in d_out for the instantiated one) is refused with
+ *    DP_ERR_UNSUPPORTED; store such layers in a 16-bit type.
  */
 #ifndef DP_BK_H
 #define DP_BK_H
@@ -112,9 +122,12 @@ dp_status dp_perex_norm(const void* a, const void* g, dp_dtype dt, int B, int T,
 
 /*
  * Cross-layer accumulation and clip factor (section 2.1; all-layer clipping, one group):
- *   norm_i = sqrt(max(0, sum_l sqnorm[l*B + i]))            (layers added in index order)
+ *   norm_i = sqrt(max(0, sum_l sqnorm[l*B + i]))            (layers added in a fixed order)
  *   DP_CLIP_STANDARD :  C_i = min(R / norm_i, 1)            (norm_i = 0 gives C_i = 1)
- *   DP_CLIP_AUTOMATIC:  C_i = R / (norm_i + stability)      (the paper prints R = 1, stability 0.01)
+ *   DP_CLIP_AUTOMATIC:  C_i = R / (norm_i + stability)      (the paper prints R = 1, stability 0.01;
+ *                                                            norm_i + stability = 0 gives C_i = 0)
+ * A sum that is NaN gives norm_i = C_i = NaN in both modes (the sample's gradient is not a
+ * number and the weighted gradient will show it); an infinite norm gives C_i = 0.
  *   sqnorm    device, [L, B] fp32 row-major
  *   C_out     device, [B] fp32
  *   norm_out  device, [B] fp32, or NULL
@@ -128,6 +141,13 @@ dp_status dp_clip_factors(const float* sqnorm, int L, int B, dp_clip_mode mode, 
  * Clip-weighted gradient (section 3, "DP gradient" without the noise term):
  *   grad[j, k] (+)= sum_i C[i] * sum_t a[i,t,j] * g[i,t,k],   j < d_in, k < d_out.
  * C[i] is applied in fp32 to sample i's exact partial product, never to the bf16 inputs.
+ * Samples with C[i] == 0 are not read.  The 16-bit kernels keep one accumulator, expressed in
+ * units of the current sample's weight, and multiply it by C[i] / C[i+1] between samples: any
+ * finite weights work whose ratios C[i] / C[j] (j the next sample with a non-zero weight) times
+ * the largest partial sum stay inside fp32 range -- in particular every set of clip factors of
+ * section 2.1, which lie in (0, 1] or in (0, R / stability]; ratios up to 1e10 either way are
+ * tested.  Beyond that range (for instance a subnormal weight next to a normal one) the result
+ * overflows to inf or NaN rather than being silently wrong.  A NaN weight gives a NaN gradient.
  *   C           device, [B] fp32
  *   grad        device, [d_in, d_out] fp32 row-major
  *   accumulate  0: overwrite grad; 1: add to it (gradient accumulation over micro-batches)
@@ -239,6 +259,24 @@ dp_status dp_bias_norm(const void* g, dp_dtype dt, int B, int T, int d_out, floa
                        float* sqnorm_out, void* stream);
 dp_status dp_clipped_bias_grad(const float* colsum, int B, int d_out, const float* C, float* grad_b,
                                int accumulate, void* stream);
+
+/*
+ * Order in which the large-tile matrix-core kernels visit their output tiles, replayed on the
+ * host (pure functions; nothing is launched).  They exist so that a test without a GPU can check
+ * that every tile of a layer is computed exactly once for any shape; the arrays may be NULL.
+ * dp_clipped_grad_tile_order: tile b of a one-layer launch of the clip-weighted gradient
+ *   (section 3, "DP gradient") starts at row tile_row0[b], column tile_col0[b] of the
+ *   [d_in, d_out] gradient; tiles are 256 x 256.
+ * dp_ghost_tile_order: workgroup b of a one-layer ghost-norm launch (appendix A.1) computes, for
+ *   sample[b], the 256 x 128 block of the two Gram matrices at token rows token_row0[b], token
+ *   columns token_col0[b] (always on or above the diagonal), and writes partial sum slot[b].
+ * Both return the number of tiles (at most `capacity` entries are written), or -1 for invalid
+ * arguments.  All pointers are HOST pointers.
+ */
+int64_t dp_clipped_grad_tile_order(int d_in, int d_out, int32_t* tile_row0, int32_t* tile_col0,
+                                   int64_t capacity);
+int64_t dp_ghost_tile_order(int T, int B, int32_t* sample, int32_t* token_row0, int32_t* token_col0,
+                            int32_t* slot, int64_t capacity);
 
 #ifdef __cplusplus
 }

@@ -73,8 +73,9 @@ def clip_factors(sqnorm: np.ndarray, mode: int, R: float, stability: float = 0.0
 
     sqnorm [L,B]: squared per-sample norms of each layer.  Returns (C [B], norm [B]).
     Standard: C_i = min(R/||g_i||, 1).  Automatic: C_i = R/(||g_i|| + stability)
-    (the paper prints the R = 1 case with stability 0.01).  A squared norm that
-    rounding pushed below zero counts as zero.
+    (the paper prints the R = 1 case with stability 0.01; with stability 0 a zero norm
+    gives C_i = 0).  A squared norm that rounding pushed below zero counts as zero; a NaN
+    norm gives a NaN factor in both modes.
     """
     total = np.sum(np.asarray(sqnorm, dtype=np.float64), axis=0)
     norm = np.sqrt(np.maximum(total, 0.0))
@@ -82,7 +83,12 @@ def clip_factors(sqnorm: np.ndarray, mode: int, R: float, stability: float = 0.0
         with np.errstate(divide="ignore"):
             C = np.minimum(np.float64(R) / norm, 1.0)
     elif mode == CLIP_AUTOMATIC:
-        C = np.float64(R) / (norm + stability)
+        # A zero gradient with no stability constant is 0/0 in the paper's normalising form
+        # (hook-free appendix: a_i^T g_i divided by its own norm).  Reading: its factor is 0 --
+        # the sample adds nothing under any finite weight.
+        den = norm + stability
+        with np.errstate(divide="ignore", invalid="ignore"):
+            C = np.where(den > 0, np.float64(R) / den, np.where(np.isnan(den), den, 0.0))
     else:
         raise ValueError("unknown clip mode")
     return C, norm

@@ -51,6 +51,8 @@ _PROTOS = {
     "dp_group_noise_threshold": (_f, [C.POINTER(_f), _i]),
     "dp_bias_norm": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp]),
     "dp_clipped_bias_grad": (_i, [_vp, _i, _i, _vp, _vp, _i, _vp]),
+    "dp_clipped_grad_tile_order": (C.c_int64, [_i, _i, _vp, _vp, C.c_int64]),
+    "dp_ghost_tile_order": (C.c_int64, [_i, _i, _vp, _vp, _vp, _vp, C.c_int64]),
 }
 EXPORTS = tuple(_PROTOS)
 for _name, (_res, _args) in _PROTOS.items():
@@ -201,3 +203,25 @@ def dp_bias_norm(g, dt, B, T, d_out, colsum, sqnorm_out, stream=None) -> None:
 def dp_clipped_bias_grad(colsum, B, d_out, Cf, grad_b, accumulate=0, stream=None) -> None:
     _check(lib.dp_clipped_bias_grad(_ptr(colsum), B, d_out, _ptr(Cf), _ptr(grad_b), accumulate, _stream(stream)),
            "dp_clipped_bias_grad")
+
+
+def dp_clipped_grad_tile_order(d_in: int, d_out: int):
+    """(tile_row0, tile_col0) numpy int32 arrays in launch order (host function)."""
+    import numpy as np
+    n = lib.dp_clipped_grad_tile_order(d_in, d_out, None, None, 0)
+    if n < 0:
+        raise DpError(DP_ERR_INVALID_ARG, "dp_clipped_grad_tile_order")
+    r, c = np.zeros(n, dtype=np.int32), np.zeros(n, dtype=np.int32)
+    lib.dp_clipped_grad_tile_order(d_in, d_out, r.ctypes.data, c.ctypes.data, n)
+    return r, c
+
+
+def dp_ghost_tile_order(T: int, B: int):
+    """(sample, token_row0, token_col0, slot) numpy int32 arrays in launch order (host function)."""
+    import numpy as np
+    n = lib.dp_ghost_tile_order(T, B, None, None, None, None, 0)
+    if n < 0:
+        raise DpError(DP_ERR_INVALID_ARG, "dp_ghost_tile_order")
+    out = [np.zeros(n, dtype=np.int32) for _ in range(4)]
+    lib.dp_ghost_tile_order(T, B, *[x.ctypes.data for x in out], n)
+    return tuple(out)

@@ -17,19 +17,26 @@ __device__ __forceinline__ float column_sum(const float* __restrict__ sqnorm, in
   return total;
 }
 
+// Clip factor of one (sample, group) from its norm (section 2.1).  A NaN norm gives a NaN
+// factor, so a sample whose gradient is not a number shows in the result instead of passing
+// unclipped (fminf would drop the NaN).  Automatic clipping with norm + stability == 0 (a zero
+// gradient and no stability constant) gives 0 rather than R/0: the sample adds nothing under any
+// weight, and an infinite weight would turn its zero gradient into NaN.
+__device__ __forceinline__ float clip_factor(float norm, int mode, float R, float stability) {
+  if (norm != norm) return norm;
+  if (mode == DP_CLIP_STANDARD) return fminf(R / norm, 1.f);     // norm == 0: R/0 = +inf -> 1
+  const float den = norm + stability;
+  return den > 0.f ? R / den : 0.f;
+}
+
 __global__ void __launch_bounds__(64)
 clip_factor_kernel(const float* __restrict__ sqnorm, int L, int B, int mode, float R,
                    float stability, float* __restrict__ C_out, float* __restrict__ norm_out) {
   const int i = blockIdx.x;                                  // one wave per sample
   const float total = column_sum(sqnorm, B, i, 0, L);
   if (threadIdx.x != 0) return;
-  const float norm = __builtin_sqrtf(fmaxf(total, 0.f));
-  float c;
-  if (mode == DP_CLIP_STANDARD)
-    c = fminf(R / norm, 1.f);          // norm == 0: R/0 = +inf -> 1
-  else
-    c = R / (norm + stability);
-  C_out[i] = c;
+  const float norm = total != total ? total : __builtin_sqrtf(fmaxf(total, 0.f));   // fmaxf drops a NaN
+  C_out[i] = clip_factor(norm, mode, R, stability);
   if (norm_out) norm_out[i] = norm;
 }
 
@@ -51,9 +58,8 @@ clip_factor_grouped_kernel(const float* __restrict__ sqnorm, int B, int mode, fl
   const int i = blockIdx.x, m = blockIdx.y;                  // one wave per (sample, group)
   const float total = column_sum(sqnorm, B, i, ga.begin[m], ga.begin[m + 1]);
   if (threadIdx.x != 0) return;
-  const float norm = __builtin_sqrtf(fmaxf(total, 0.f));
-  const float R = ga.R[m];
-  const float c = mode == DP_CLIP_STANDARD ? fminf(R / norm, 1.f) : R / (norm + stability);
+  const float norm = total != total ? total : __builtin_sqrtf(fmaxf(total, 0.f));   // fmaxf drops a NaN
+  const float c = clip_factor(norm, mode, ga.R[m], stability);
   const size_t o = (size_t)(ga.first_group + m) * B + i;
   C_out[o] = c;
   if (norm_out) norm_out[o] = norm;

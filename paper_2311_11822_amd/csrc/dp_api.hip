@@ -5,6 +5,7 @@
 #include <vector>
 
 #include "dp_internal.h"
+#include "tile_order.h"
 
 using namespace dpbk;
 
@@ -41,26 +42,31 @@ int tiles_per_sample(int path, const dp_layer& ly) {
 
 // Launches the norm kernels of one path for the listed layers, in chunks of kMaxGroup.
 // part_begin[l] is the layer's first slot in the partial-sum workspace.
-enum NormKernel { kGhostBig, kGhostSmall, kPerex };
+enum NormKernel { kGhostBig = 0, kGhostSmall = 1, kPerex = 2 };
 
-dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, std::vector<int> which,
-                        const std::vector<int64_t>& part_begin, dp_dtype dt, int B, float* partials,
+dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, int n_which,
+                        const int64_t* part_begin, dp_dtype dt, int B, float* partials,
                         float* sqnorm_out, hipStream_t s) {
   // A tile's length is the contraction it runs over (d_in + d_out for the ghost norm, T for the
   // instantiated one).  Longest first: workgroups are handed out in order, so the short tiles
   // fill the end of the launch.  Each layer writes its own workspace slots and sqnorm row, so
-  // the order inside a launch is free.
-  std::stable_sort(which.begin(), which.end(), [&](int x, int y) {
-    const int64_t lx = kernel == kPerex ? layers[x].T : (int64_t)layers[x].d_in + layers[x].d_out;
-    const int64_t ly = kernel == kPerex ? layers[y].T : (int64_t)layers[y].d_in + layers[y].d_out;
-    return lx > ly;
-  });
-  for (size_t begin = 0; begin < which.size(); begin += kMaxGroup) {
+  // the order inside a launch is free.  (Stable insertion sort in place: this path must not
+  // touch the heap, see dp_norms_multi_static.)
+  auto length = [&](int l) {
+    return kernel == kPerex ? (int64_t)layers[l].T : (int64_t)layers[l].d_in + layers[l].d_out;
+  };
+  for (int i = 1; i < n_which; ++i) {
+    const int x = which[i];
+    int j = i;
+    for (; j > 0 && length(which[j - 1]) < length(x); --j) which[j] = which[j - 1];
+    which[j] = x;
+  }
+  for (int begin = 0; begin < n_which; begin += kMaxGroup) {
     GroupArgs ga;
     ga.B = B;
     ga.accumulate = 0;
     ga.f16 = dt == DP_F16;
-    ga.n_layers = (int)std::min<size_t>(kMaxGroup, which.size() - begin);
+    ga.n_layers = std::min(kMaxGroup, n_which - begin);
     int64_t blocks = 0;
     for (int j = 0; j < ga.n_layers; ++j) {
       const int l = which[begin + j];
@@ -91,31 +97,39 @@ dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, std::vector<i
 }
 
 // Total partial-sum slots, or -1 if a layer is invalid.
-int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, std::vector<int64_t>* begin) {
+int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, int64_t* begin) {
   if (!layers || L <= 0 || B <= 0) return -1;
   int64_t total = 0;
   for (int l = 0; l < L; ++l) {
     if (!dims_ok(dt, B, layers[l].T, layers[l].d_in, layers[l].d_out)) return -1;
     if (layers[l].path != DP_PATH_GHOST && layers[l].path != DP_PATH_PEREX) return -1;
-    if (begin) begin->push_back(total);
+    if (begin) begin[l] = total;
     if (dt != DP_F32) total += (int64_t)tiles_per_sample(layers[l].path, layers[l]) * B;
     if (total > INT32_MAX) return -1;
   }
   return total;
 }
 
+// begin: room for L values; idx: room for 3 L values (the layers of each kernel).  The caller
+// provides both so that this function never touches the heap.
 dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
-                     size_t ws_bytes, hipStream_t s) {
+                     size_t ws_bytes, hipStream_t s, int64_t* begin, int* idx) {
   if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!sqnorm_out) return DP_ERR_INVALID_ARG;
-  std::vector<int64_t> begin;
-  const int64_t slots = norm_slots(layers, L, dt, B, &begin);
+  const int64_t slots = norm_slots(layers, L, dt, B, begin);
   if (slots < 0) return DP_ERR_INVALID_ARG;
   for (int l = 0; l < L; ++l) {
     dp_status st = check_layer_ptrs(layers[l].a, layers[l].g);
     if (st != DP_OK) return st;
   }
   if (dt == DP_F32) {
+    for (int l = 0; l < L; ++l) {
+      const dp_layer& ly = layers[l];
+      const __int128 work = ly.path == DP_PATH_GHOST
+                                ? (__int128)ly.T * ly.T / 2 * ((int64_t)ly.d_in + ly.d_out)
+                                : (__int128)ly.T * ly.d_in * ly.d_out;
+      if (work > kF32MaxWork) return DP_ERR_UNSUPPORTED;
+    }
     for (int l = 0; l < L; ++l) {
       const dp_layer& ly = layers[l];
       const float* a = static_cast<const float*>(ly.a);
@@ -129,19 +143,26 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
   }
   if (!ws || ws_bytes < (size_t)slots * sizeof(float)) return DP_ERR_WORKSPACE;
   if (!aligned16(ws)) return DP_ERR_INVALID_ARG;
-  std::vector<int> ghost_big, ghost_small, perex;
+  int* list[3] = {idx, idx + L, idx + 2 * L};          // kGhostBig, kGhostSmall, kPerex
+  int count[3] = {0, 0, 0};
   for (int l = 0; l < L; ++l) {
-    if (layers[l].path == DP_PATH_PEREX)
-      perex.push_back(l);
-    else
-      (ghost_uses_big(layers[l]) ? ghost_big : ghost_small).push_back(l);
+    const int k = layers[l].path == DP_PATH_PEREX ? kPerex : ghost_uses_big(layers[l]) ? kGhostBig : kGhostSmall;
+    list[k][count[k]++] = l;
   }
   float* partials = static_cast<float*>(ws);
-  dp_status st = run_norm_path(kGhostBig, layers, ghost_big, begin, dt, B, partials, sqnorm_out, s);
-  if (st != DP_OK) return st;
-  st = run_norm_path(kGhostSmall, layers, ghost_small, begin, dt, B, partials, sqnorm_out, s);
-  if (st != DP_OK) return st;
-  return run_norm_path(kPerex, layers, perex, begin, dt, B, partials, sqnorm_out, s);
+  for (int k = 0; k < 3; ++k) {
+    dp_status st = run_norm_path((NormKernel)k, layers, list[k], count[k], begin, dt, B, partials, sqnorm_out, s);
+    if (st != DP_OK) return st;
+  }
+  return DP_OK;
+}
+
+dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
+                     size_t ws_bytes, hipStream_t s) {
+  if (!layers || L <= 0) return DP_ERR_INVALID_ARG;
+  std::vector<int64_t> begin(L);
+  std::vector<int> idx(3 * (size_t)L);
+  return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, s, begin.data(), idx.data());
 }
 
 dp_status single_norm(dp_path path, const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
@@ -449,6 +470,47 @@ dp_status dp_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_block
   if (n_blocks == 0) return DP_OK;
   if (first_block + n_blocks < first_block) return DP_ERR_INVALID_ARG;
   return launch_philox_blocks(out, first_block, n_blocks, seed, step, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------
+// Tile orders of the large-tile kernels, replayed on the host (pure functions, for tests).
+// ---------------------------------------------------------------------------------
+extern "C" {
+
+int64_t dp_clipped_grad_tile_order(int d_in, int d_out, int32_t* tile_row0, int32_t* tile_col0,
+                                   int64_t capacity) {
+  if (d_in <= 0 || d_out <= 0 || capacity < 0) return -1;
+  const int64_t n = clipped_grad_big_tiles(d_in, d_out);
+  if (n > INT32_MAX / 2) return -1;
+  const int n_tail = clipped_grad_big_tail_tiles((int)n), n_main = (int)n - n_tail;
+  const int tiles_m = (d_in + 255) / 256, tiles_n = (d_out + 255) / 256;
+  for (int64_t b = 0; b < n && b < capacity; ++b) {
+    // workgroups of the large-tile kernel first, then the tiles left to the sub-tile kernel
+    const int t = b < n_main ? grad_logical_tile((int)b, n_main) : (int)b;
+    int tm, tn;
+    grad_tile_of(tiles_m, tiles_n, t, tm, tn);
+    if (tile_row0) tile_row0[b] = tm * 256;
+    if (tile_col0) tile_col0[b] = tn * 256;
+  }
+  return n;
+}
+
+int64_t dp_ghost_tile_order(int T, int B, int32_t* sample, int32_t* token_row0, int32_t* token_col0,
+                            int32_t* slot, int64_t capacity) {
+  if (T <= 0 || B <= 0 || capacity < 0) return -1;
+  const int tps = ghost_big_tiles_per_sample(T);
+  const int64_t n = (int64_t)tps * B;
+  if (n > INT32_MAX / 2) return -1;
+  for (int64_t b = 0; b < n && b < capacity; ++b) {
+    const GhostTile t = ghost_tile_of(T, B, tps, ghost_logical_tile((int)b, (int)n));
+    if (sample) sample[b] = t.sample;
+    if (token_row0) token_row0[b] = t.I * 256;
+    if (token_col0) token_col0[b] = t.J * 128;
+    if (slot) slot[b] = t.slot;
+  }
+  return n;
 }
 
 }  // extern "C"

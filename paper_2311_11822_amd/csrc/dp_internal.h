@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "dp_bk.h"
 #include "philox.h"
 
@@ -80,19 +82,27 @@ __device__ __forceinline__ int layer_of(const GroupArgs& ga, int id) {
   return lo;
 }
 
+// The fp32 norm kernels run one workgroup per sample on the vector ALUs; layers whose norm needs
+// more multiply-adds per sample than this are refused (DP_ERR_UNSUPPORTED) instead of running
+// for seconds.  2^28 multiply-adds take a few tens of milliseconds.
+constexpr int64_t kF32MaxWork = (int64_t)1 << 28;
+
 inline dp_status hip_status(hipError_t e) { return e == hipSuccess ? DP_OK : DP_ERR_HIP; }
 
 // Kernels that need more than 64 KiB of LDS must be told so once per device; `done` is the
-// caller's per-kernel table of devices already prepared.
+// caller's per-kernel table of devices already prepared.  These tables are the library's only
+// mutable host state: flags that go from false to true once, so two threads that race on one at
+// worst both make the (idempotent) attribute call.
 constexpr int kMaxDevices = 64;
+using ReadyTable = std::atomic<bool>[kMaxDevices];
 template <class K>
-dp_status allow_big_lds(K kernel, int bytes, bool (&done)[kMaxDevices]) {
+dp_status allow_big_lds(K kernel, int bytes, ReadyTable& done) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DP_ERR_HIP;
-  if (done[dev]) return DP_OK;
+  if (done[dev].load(std::memory_order_acquire)) return DP_OK;
   dp_status st = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
-  if (st == DP_OK) done[dev] = true;
+  if (st == DP_OK) done[dev].store(true, std::memory_order_release);
   return st;
 }
 
@@ -133,6 +143,8 @@ bool ghost_big_supports(int T, int d, int p);
 dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream_t s);
 // 256x256-tile kernel with direct global->LDS loads (grad_gemm.hip).
 int clipped_grad_big_tiles(int d, int p);
+// Of a launch of n large tiles, how many (the last ones) go to the sub-tile kernel.
+int clipped_grad_big_tail_tiles(int n);
 bool clipped_grad_big_supports(int T, int d, int p);
 // noise == nullptr: gradients only.
 dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, const NoiseArgs* noise,

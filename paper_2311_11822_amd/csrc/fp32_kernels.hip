@@ -1,6 +1,9 @@
 // fp32-input forms of the three contractions, for small layers (the tiny all-fp32
 // configuration).  Plain vector-ALU code: these shapes are launch-latency bound, so there
 // is nothing for the matrix cores to win.  Reductions run in a fixed order (no atomics).
+// The norm kernels run one workgroup per sample, so they are meant for layers of a few
+// thousand elements; the host side refuses fp32 layers beyond kF32MaxWork multiply-adds per
+// sample (DP_ERR_UNSUPPORTED) rather than run for seconds.
 #include "dp_internal.h"
 
 namespace dpbk {
@@ -71,6 +74,7 @@ clipped_grad_f32_kernel(const float* __restrict__ a, const float* __restrict__ g
   const int j = (int)(q / p), k = (int)(q % p);
   float total = 0.f;
   for (int i = 0; i < B; ++i) {
+    if (C[i] == 0.f) continue;                 // a masked sample is not read, as in the 16-bit kernels
     const float* ai = a + (size_t)i * T * d;
     const float* gi = g + (size_t)i * T * p;
     float s = 0.f;

@@ -23,6 +23,7 @@
 #include <type_traits>
 
 #include "dp_internal.h"
+#include "tile_order.h"
 
 namespace dpbk {
 
@@ -89,40 +90,14 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   const unsigned lds0 = (unsigned)(uintptr_t)lds_raw;
 
-  // XCD-aware order.  Workgroup b runs on XCD b % 8 (round-robin dispatch), and the tiles of one
-  // sample read the same token rows: each XCD takes chunks of 32 consecutive tile numbers, so
-  // that a sample's tiles meet in one L2 instead of being fetched by up to eight.  Tiles of
-  // different layers differ in length (d_in + d_out), so the chunks are dealt out cyclically
-  // and the deal rotates by one XCD per round of 256 tiles: every XCD then sees every part of
-  // the launch, whatever the period of the layer pattern (contiguous eighths of the launch
-  // leave the XCDs with unequal work).
-  int logical;
-  {
-    constexpr int CHUNK = 32, ROUND = 8 * CHUNK;
-    const int n = ga.total_blocks;
-    const int round = blockIdx.x / ROUND, base = round * ROUND, qd = blockIdx.x - base;
-    const int xcd = qd & 7, idx = qd >> 3;
-    if (base + ROUND <= n) {
-      logical = base + ((xcd - round) & 7) * CHUNK + idx;
-    } else {                                      // last, partial round: contiguous eighths
-      const int m = n - base, per = m >> 3, rest = m & 7;
-      logical = base + (xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx);
-    }
-  }
+  // XCD-aware order of the launch's tiles and of a layer's tiles: see tile_order.h.
+  const int logical = ghost_logical_tile(blockIdx.x, ga.total_blocks);
   const int l = layer_of(ga, logical);
   const GroupLayer& ly = ga.layer[l];
-  const int local = logical - ly.tile_begin;
-  const int sample = local / ly.tiles_per_sample;
-  int q = local % ly.tiles_per_sample;
   const int T = ly.T;
-  // q enumerates tiles (I, J), J >= 2I, row by row; a tile row I has nj - 2I tiles.
-  const int nj = (T + TJ - 1) / TJ;
-  int I = 0;
-  while (q >= nj - 2 * I) {
-    q -= nj - 2 * I;
-    ++I;
-  }
-  const int J = 2 * I + q;
+  const GhostTile gt = ghost_tile_of(T, ga.B, ly.tiles_per_sample, logical - ly.tile_begin);
+  const int sample = gt.sample, I = gt.I, J = gt.J;
+  const int q = J - 2 * I;                        // position in the tile row: 0 holds the diagonal
   const int r0 = I * TI, c0 = J * TJ;
   const bool inside = q < 2;                      // column block is one half of the row block
 
@@ -388,7 +363,7 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   float* red = reinterpret_cast<float*>(lds_raw);
   if (lane == 0) red[wave] = s;
   __syncthreads();
-  if (tid == 0) partials[ly.part_begin + local] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (tid == 0) partials[ly.part_begin + gt.slot] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 }  // namespace
@@ -408,7 +383,7 @@ bool ghost_big_supports(int T, int d, int p) {
 
 template <bool COMPACT, bool F16>
 dp_status launch_plan(const GroupArgs& ga, float* partials, hipStream_t s) {
-  static bool ready[kMaxDevices] = {};
+  static ReadyTable ready;
   auto kernel = ghost_big_kernel<COMPACT, F16>;
   dp_status st = allow_big_lds(kernel, Plan<COMPACT>::LDS_BYTES, ready);
   if (st != DP_OK) return st;

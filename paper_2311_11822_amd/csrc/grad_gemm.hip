@@ -26,6 +26,7 @@
 #include <type_traits>
 
 #include "dp_internal.h"
+#include "tile_order.h"
 #include "tn_tile.h"
 
 namespace dpbk {
@@ -84,30 +85,15 @@ struct Frag {
 
 #define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
-// Tile t of the launch -> layer and tile origin.  Inside a layer, tiles are numbered so that
-// 32 consecutive numbers form a patch of 4 tile rows x 8 tile columns and 8 consecutive
-// patches form a 16 x 16 super-patch (clamped at the layer's edges): 32 compute units of one
-// XCD then pull 12 operand panels per 32 tiles through that XCD's L2, and the 8 XCDs 32 panels
-// per 256 tiles through the memory-side cache.
+// Tile t of the launch -> layer and tile origin (order inside a layer: tile_order.h).
 __device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& layer, int& m0, int& n0) {
   const int l = layer_of(ga, t);
   layer = l;
   const GroupLayer& ly = ga.layer[l];
-  int rem = t - ly.tile_begin;
-  const int tiles_m = (ly.d_in + BM - 1) / BM, tiles_n = (ly.d_out + BN - 1) / BN;
-  const int sr = min(rem / (16 * tiles_n), (tiles_m - 1) / 16);      // super-patch row
-  rem -= sr * 16 * tiles_n;
-  const int hm = min(16, tiles_m - 16 * sr);
-  const int sc = min(rem / (hm * 16), (tiles_n - 1) / 16);           // super-patch column
-  rem -= sc * hm * 16;
-  const int wn = min(16, tiles_n - 16 * sc);
-  const int pr = min(rem / (4 * wn), (hm - 1) / 4);                  // patch row inside it
-  rem -= pr * 4 * wn;
-  const int ph = min(4, hm - 4 * pr);
-  const int pc = min(rem / (ph * 8), (wn - 1) / 8);                  // patch column
-  rem -= pc * ph * 8;
-  m0 = (16 * sr + 4 * pr + rem % ph) * BM;
-  n0 = (16 * sc + 8 * pc + rem / ph) * BN;
+  int tm, tn;
+  grad_tile_of((ly.d_in + BM - 1) / BM, (ly.d_out + BN - 1) / BN, t - ly.tile_begin, tm, tn);
+  m0 = tm * BM;
+  n0 = tn * BN;
 }
 
 // The kernel's copy of what tile_noise needs, read once from the kernel arguments into registers.
@@ -178,18 +164,7 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, 
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   const unsigned lds0 = (unsigned)(uintptr_t)lds_raw;
 
-  // XCD-aware order.  Workgroup b runs on XCD b % 8 (round-robin dispatch) and about 256
-  // consecutive ids are resident at a time.  Within each run of 256 ids, XCD x gets the x-th
-  // group of 32 consecutive tile numbers, i.e. one 4 x 8 patch of locate_tile's numbering, and
-  // the eight XCDs together one 16 x 16 super-patch.
-  int logical;
-  {
-    constexpr int ROUND = 256;
-    const int base = (blockIdx.x / ROUND) * ROUND, q = blockIdx.x - base;
-    const int n = min(ROUND, ga.total_blocks - base);
-    const int per = n >> 3, rest = n & 7, xcd = q & 7, idx = q >> 3;
-    logical = base + (xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx);
-  }
+  const int logical = grad_logical_tile(blockIdx.x, ga.total_blocks);     // XCD-aware: tile_order.h
   int l, m0, n0;
   locate_tile(ga, logical, l, m0, n0);
   const GroupLayer& ly = ga.layer[l];
@@ -665,19 +640,23 @@ bool clipped_grad_big_supports(int T, int d, int p) {
 #endif
 constexpr int kRound = 256;           // compute units = large-tile workgroups resident at a time
 
+int clipped_grad_big_tail_tiles(int n) {
+  const int n_tail = n % kRound;
+  return n_tail > DP_TAIL_MAX ? 0 : n_tail;
+}
+
 template <bool F16, bool NOISE>
 dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, const NoiseArgs& na,
                                           hipStream_t s) {
   auto big = clipped_grad_big_kernel<F16, NOISE>;
   auto tail = clipped_grad_tail_kernel<F16, NOISE>;
-  static bool ready_big[kMaxDevices] = {}, ready_tail[kMaxDevices] = {};
+  static ReadyTable ready_big, ready_tail;
   dp_status st0 = allow_big_lds(big, LDS_BYTES, ready_big);
   if (st0 != DP_OK) return st0;
   st0 = allow_big_lds(tail, (int)TailShape::LDS_BYTES, ready_tail);
   if (st0 != DP_OK) return st0;
   const int n = ga.total_blocks;
-  int n_tail = n % kRound;
-  if (n_tail > DP_TAIL_MAX) n_tail = 0;
+  const int n_tail = clipped_grad_big_tail_tiles(n);
   if (n > n_tail) {
     GroupArgs main_args = ga;
     main_args.total_blocks = n - n_tail;

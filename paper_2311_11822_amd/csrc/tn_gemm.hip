@@ -119,12 +119,6 @@ norm_reduce_kernel(const GroupArgs ga, const float* __restrict__ partials, float
 using GradShape = TnShape<DP_GRAD_SHAPE>;
 using PerexShape = TnShape<128, 128, 64, 2, 2>;
 
-template <class K>
-dp_status allow_lds(K kernel, size_t bytes) {
-  return hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-}
-
 }  // namespace
 
 int perex_tiles_per_sample(int d, int p) {
@@ -138,7 +132,8 @@ int clipped_grad_tiles(int d, int p) {
 template <bool F16>
 dp_status launch_clipped_grad_group_t(const GroupArgs& ga, const float* C, hipStream_t s) {
   auto kernel = clipped_grad_kernel<GradShape, F16>;
-  dp_status st = allow_lds(kernel, GradShape::LDS_BYTES);
+  static ReadyTable ready;
+  dp_status st = allow_big_lds(kernel, (int)GradShape::LDS_BYTES, ready);
   if (st != DP_OK) return st;
   hipLaunchKernelGGL(kernel, dim3(ga.total_blocks), dim3(GradShape::NT), GradShape::LDS_BYTES, s, ga, C);
   return hip_status(hipGetLastError());
@@ -147,7 +142,8 @@ dp_status launch_clipped_grad_group_t(const GroupArgs& ga, const float* C, hipSt
 template <bool F16>
 dp_status launch_perex_group_t(const GroupArgs& ga, float* partials, hipStream_t s) {
   auto kernel = perex_norm_kernel<PerexShape, F16>;
-  dp_status st = allow_lds(kernel, PerexShape::LDS_BYTES);
+  static ReadyTable ready;
+  dp_status st = allow_big_lds(kernel, (int)PerexShape::LDS_BYTES, ready);
   if (st != DP_OK) return st;
   hipLaunchKernelGGL(kernel, dim3(ga.total_blocks), dim3(PerexShape::NT), PerexShape::LDS_BYTES, s, ga,
                      partials);

@@ -3,6 +3,7 @@ declares, and its pure host functions and argument validation behave as document
 import os
 import re
 
+import numpy as np
 import pytest
 
 import synth_inputs as si
@@ -104,3 +105,64 @@ def test_validation_of_the_later_entry_points(dp):
     assert lib.dp_bias_norm(fake, 1, 1, 8, 12, fake, fake, None) == INV             # 16-bit row not 16 B
     assert lib.dp_clipped_bias_grad(fake, 1, 8, None, fake, 0, None) == INV
     assert lib.dp_clipped_bias_grad(fake, 1, 8, fake, fake, 2, None) == INV
+
+
+# ----------------------------------------------------------------------------
+# tile orders of the large-tile kernels: every tile exactly once, for any shape
+# ----------------------------------------------------------------------------
+
+GRAD_SHAPES = sorted({(d, p) for w in si.WORKLOADS.values() for d, p in w.layers if d >= 128} |
+                     {(136, 264), (4360, 3848), (1800, 1544), (256, 256), (257, 255), (12288, 256), (256, 49152),
+                      (4352, 8448), (8704, 4352), (17 * 256, 33 * 256), (70 * 256 - 8, 41 * 256 + 8)})
+
+
+@pytest.mark.parametrize("d,p", GRAD_SHAPES)
+def test_gradient_tile_order_is_a_bijection(dp, d, p):
+    r, c = dp.dp_clipped_grad_tile_order(d, p)
+    tiles_m, tiles_n = -(-d // 256), -(-p // 256)
+    assert len(r) == tiles_m * tiles_n
+    assert np.all(r % 256 == 0) and np.all(c % 256 == 0)
+    seen = np.zeros((tiles_m, tiles_n), dtype=np.int64)
+    np.add.at(seen, (r // 256, c // 256), 1)
+    assert np.all(seen == 1)
+
+
+def test_gradient_tile_order_keeps_patches_together(dp):
+    # the 32 tiles one XCD takes in a round (workgroups x, x + 8, ... of a run of 256) form a
+    # patch of at most 4 tile rows x 8 tile columns
+    r, c = dp.dp_clipped_grad_tile_order(12288, 36864)
+    for base in (0, 256, 256 * 13):
+        for x in range(8):
+            ids = base + x + 8 * np.arange(32)
+            rows, cols = np.unique(r[ids] // 256), np.unique(c[ids] // 256)
+            assert len(rows) <= 4 and len(cols) <= 8 and len(rows) * len(cols) == 32
+
+
+@pytest.mark.parametrize("T,B", [(2048, 4), (512, 8), (256, 16), (96, 3), (130, 2), (300, 2), (1024, 3), (1025, 3),
+                                 (1152, 2), (2049, 1), (3000, 2), (4096, 2), (5000, 1), (8192, 1), (2304, 5)])
+def test_ghost_tile_order_is_a_bijection(dp, T, B):
+    sample, r0, c0, slot = dp.dp_ghost_tile_order(T, B)
+    nj, ni = -(-T // 128), -(-T // 256)
+    tps = sum(nj - 2 * I for I in range(ni))
+    assert len(sample) == B * tps
+    I, J = r0 // 256, c0 // 128
+    assert np.all((sample >= 0) & (sample < B) & (I >= 0) & (I < ni) & (J >= 2 * I) & (J < nj))
+    seen = np.zeros((B, ni, nj), dtype=np.int64)
+    np.add.at(seen, (sample, I, J), 1)
+    want = np.zeros((ni, nj), dtype=np.int64)
+    for i in range(ni):
+        want[i, 2 * i:] = 1
+    assert np.all(seen == want[None])
+    # partial-sum slots: each used once, and a sample's slots are contiguous
+    assert sorted(slot.tolist()) == list(range(B * tps))
+    assert np.all(slot // tps == sample)
+
+
+def test_ghost_tile_order_groups_rows_for_long_sequences(dp):
+    # T = 2048: a run of 32 consecutive workgroups of one XCD in the first part of a layer is one
+    # off-diagonal super-block of one sample: 4 tile rows x 8 tile columns, 2048 distinct token rows
+    sample, r0, c0, _ = dp.dp_ghost_tile_order(2048, 4)
+    ids = 0 + 8 * np.arange(32)                       # XCD 0, first round
+    assert len(np.unique(sample[ids])) == 1
+    assert len(np.unique(r0[ids])) == 4 and len(np.unique(c0[ids])) == 8
+    assert np.all(c0[ids] >= 1024) and np.all(r0[ids] < 1024)

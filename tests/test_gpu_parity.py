@@ -370,6 +370,115 @@ def test_standard_clipping_takes_both_branches(dp, Pipe):
         assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, C)) <= 1e-4
 
 
+@pytest.mark.parametrize("with_wide_layer", [False, True])
+def test_stack_with_three_sequence_lengths(dp, Pipe, with_wide_layer):
+    # T is a per-layer quantity (section 3: a_l in R^{B x T_l x d_l}); one grouped launch holds
+    # layers of different T.  Ghost norm: layers with T = 96 and 256 ride in a launch that takes
+    # the general plan because of the T = 320 layer; one layer takes the instantiated norm.
+    # Gradient: 19 tiles (all computed as sub-tiles) or, with the wide T = 64 layer, 75 tiles
+    # (all computed as 256 x 256 tiles), k extents 64 to 320 in one launch.
+    dims = [(128, 320), (256, 640), (384, 1280), (264, 392)] + ([(1800, 1544)] if with_wide_layer else [])
+    Ts = [96, 256, 320, 256] + ([64] if with_wide_layer else [])
+    B = 3
+    layers = []
+    for l, ((d, p), T) in enumerate(zip(dims, Ts)):
+        w = si.small_workload("mt", si.BF16, B, T, [(d, p)], data_seed=100 + l)
+        layers.append(si.gen_layer(w, 0))
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    assert [T for T, _, _ in pipe.dims] == Ts
+    assert pipe.paths[:4] == [0, 0, 0, 1]
+    pipe.norms()
+    pipe.clip(dp.DP_CLIP_AUTOMATIC, 1.0, 0.01)
+    pipe.grad()
+    sqn = np.stack([o.perex_sqnorm(a, g) for a, g in l64])
+    assert rel(host(pipe.sqnorm), sqn) <= TOL_BF16_NORM
+    C, _ = o.clip_factors(sqn, o.CLIP_AUTOMATIC, 1.0, 0.01)
+    assert rel(host(pipe.C), C) <= TOL_BF16_NORM
+    Cg = host(pipe.C).astype(np.float64)              # the weights the kernels actually used
+    clean = []
+    for l, (a, g) in enumerate(l64):
+        G = o.clipped_grad(a, g, Cg)
+        assert frob(host(pipe.grads[l]), G) <= 1e-5
+        clean.append(G)
+    # the same stack with the noise added in the gradient pass
+    sigma, R, seed, step = 0.5, 1.0, 17, 3
+    two_pass = pipe.flat.clone()
+    dp.dp_add_noise(two_pass, 0, pipe.psi, sigma, R, seed, step)
+    pipe.flat.fill_(1.0)
+    pipe.grad_noise(sigma, R, seed, step, 0, pipe.psi)
+    assert torch.equal(pipe.flat, two_pass)
+    z = o.normals(seed, step, 0, pipe.psi)
+    want = np.concatenate([G.reshape(-1) for G in clean]) + sigma * R * z
+    have = host(pipe.flat).astype(np.float64)
+    assert np.all(np.abs(have - want) <= 2e-5 * sigma * R * np.maximum(1.0, np.abs(z)) + 1e-4 * np.abs(want - sigma * R * z))
+
+
+@pytest.mark.parametrize("B,T,d,p", [
+    (6, 64, 1800, 1544),     # one short round of 256 x 256 tiles
+    (6, 96, 392, 520),       # sub-tile kernel only
+    (6, 50, 136, 264),       # T not a multiple of 32: the 8-wave kernel
+    (6, 32, 4360, 3848),     # a full round of large tiles plus sub-tiles
+])
+def test_weight_ratios_across_ten_decades(dp, B, T, d, p):
+    # The kernels hold one accumulator in units of the current sample's weight and multiply it by
+    # C_i / C_{i+1} between samples: ratios from 1e-10 to 1e10 in one batch, in both directions
+    w = si.small_workload("wr", si.BF16, B, T, [(d, p)])
+    a, g = si.gen_layer(w, 0)
+    a64, g64 = si.to_f64(a), si.to_f64(g)
+    for C in ([1e-8, 1e2, 1e-8, 3e-3, 1e2, 1.0], [1e2, 1e-8, 1e2, 1.0, 1e-8, 1e-8], [1e-8] * 6, [-1.0, 1e2, 0.0, -1e-8, 1.0, 1e2]):
+        C = np.array(C, dtype=np.float32)
+        grad = torch.full((d, p), 5.0, dtype=torch.float32, device="cuda")
+        dp.dp_clipped_grad(dev(a), dev(g), dp.DP_BF16, B, T, d, p, dev(C), grad, 0)
+        G = o.clipped_grad(a64, g64, C.astype(np.float64))
+        got = host(grad)
+        assert np.all(np.isfinite(got))
+        assert frob(got, G) <= 1e-5, C
+
+
+def test_calls_on_a_side_stream(dp, Pipe):
+    # every entry point enqueues on the stream it is given: the whole path on a non-default
+    # stream, with the default stream kept busy on an unrelated buffer
+    w = si.small_workload("st", si.BF16, 3, 160, [(136, 264), (392, 520), (264, 72)], clip_mode=si.CLIP_AUTOMATIC)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())          # inputs were uploaded on the current stream
+    busy = torch.zeros(1 << 24, device="cuda")
+    for _ in range(8):
+        busy.add_(1.0)                                     # default-stream work in flight meanwhile
+    off, cnt = 0, pipe.psi
+    pipe.step(w.clip_mode, w.R, 0.5, w.stability, 5, 1, off, cnt, stream=side, fused=False)
+    side.synchronize()
+    ref = o.private_gradient(l64, w.clip_mode, w.R, 0.5, w.stability, 5, 1, off, cnt)
+    assert rel(pipe.C.cpu().numpy(), ref["C"]) <= TOL_BF16_NORM
+    np.testing.assert_allclose(pipe.flat.cpu().numpy(), ref["flat"], rtol=0, atol=1e-4)
+    two = pipe.flat.clone()
+    pipe.step(w.clip_mode, w.R, 0.5, w.stability, 5, 1, off, cnt, stream=side, fused=True)
+    side.synchronize()
+    assert torch.equal(pipe.flat, two)
+    torch.cuda.synchronize()
+    assert float(busy[0]) == 8.0
+
+
+def test_clip_factor_corner_values_on_device(dp):
+    # zero norm without a stability constant -> 0; NaN squared norm -> NaN factor in both modes;
+    # infinite norm -> factor 0
+    sqn = np.array([[0.0, 4.0, np.nan, np.inf, -1e-9]], dtype=np.float32)
+    for mode, stab in ((0, 0.01), (1, 0.0), (1, 0.01)):
+        Cd = torch.zeros(5, dtype=torch.float32, device="cuda")
+        nd = torch.zeros(5, dtype=torch.float32, device="cuda")
+        dp.dp_clip_factors(dev(sqn), 1, 5, mode, 1.0, stab, Cd, nd)
+        C, norm = o.clip_factors(sqn.astype(np.float64), mode, 1.0, stab)
+        got = host(Cd)
+        assert np.isnan(got[2]) and np.isnan(C[2]) and got[3] == 0.0 and C[3] == 0.0
+        np.testing.assert_allclose(got[[0, 1, 4]], C[[0, 1, 4]], rtol=TOL_F32)
+        Cg = torch.zeros((1, 5), dtype=torch.float32, device="cuda")
+        dp.dp_clip_factors_grouped(dev(sqn), 1, 5, [0, 1], [1.0], mode, stab, Cg)
+        np.testing.assert_array_equal(host(Cg)[0], got)
+
+
 # ----------------------------------------------------------------------------
 # full-size workloads
 # ----------------------------------------------------------------------------
@@ -404,6 +513,28 @@ def sampled_grad_check(w, layers, C, pipe, full_layers=(), n_samples=2048, seed=
     return worst
 
 
+def block_grid_check(w, layers, C, pipe, seed=11):
+    """Gradient before noise, one seeded entry in every 64 x 64 block of every layer (64 x 64 is
+    the smallest unit a workgroup of any gradient kernel writes): one row index per 64-row band,
+    one column index per 64-column band; those columns of a and g are gathered and the oracle's
+    clip-weighted gradient of the gathered operands is the grid of expected entries."""
+    worst = 0.0
+    rng = np.random.default_rng(seed)
+    for l, (a, g) in enumerate(layers):
+        d, p = w.layers[l]
+        rows = np.array([r0 + rng.integers(0, min(64, d - r0)) for r0 in range(0, d, 64)])
+        cols = np.array([c0 + rng.integers(0, min(64, p - c0)) for c0 in range(0, p, 64)])
+        want = o.clipped_grad(si.to_f64(np.ascontiguousarray(a[:, :, rows])),
+                              si.to_f64(np.ascontiguousarray(g[:, :, cols])), C)
+        have = host(pipe.grads[l][torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+        assert have.shape == want.shape
+        worst = max(worst, frob(have, want))
+        # entry by entry too: one wrong or unwritten block must not hide in the Frobenius norm
+        scale = np.sqrt(np.mean(want * want))
+        assert np.max(np.abs(have - want)) <= 1e-3 * scale, (l, float(np.max(np.abs(have - want))), scale)
+    return worst
+
+
 def run_workload(dp, Pipe, name, full_layers=()):
     w = si.WORKLOADS[name]
     layers = gen(w)
@@ -421,6 +552,7 @@ def run_workload(dp, Pipe, name, full_layers=()):
     assert rel(host(pipe.norm), norm) <= TOL_BF16_NORM
     assert rel(host(pipe.C), C) <= TOL_BF16_NORM
     assert sampled_grad_check(w, layers, C, pipe, full_layers) <= TOL_BF16_GRAD
+    assert block_grid_check(w, layers, C, pipe) <= TOL_BF16_GRAD
     # noise on the rank's shard only; checked on the head, the tail and a window inside
     off, cnt = w.noise_range()
     before = pipe.flat.clone()

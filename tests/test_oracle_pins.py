@@ -166,6 +166,15 @@ def test_clip_degenerate_cases():
     assert list(C) == [1.0, 1.0]                        # R = inf: nothing is clipped
     C, _ = o.clip_factors(np.array([[0.0]]), o.CLIP_AUTOMATIC, 1.0)
     assert C[0] == pytest.approx(100.0)
+    # no stability constant (the normalising form of the hook-free appendix): every non-zero
+    # gradient comes out with norm R exactly; a zero gradient gets factor 0, not R/0
+    C, norm = o.clip_factors(np.array([[0.0, 4.0, 1e-30]]), o.CLIP_AUTOMATIC, 3.0, 0.0)
+    assert C[0] == 0.0
+    np.testing.assert_allclose((C * norm)[1:], 3.0, rtol=1e-15)
+    # a gradient that is not a number shows in its factor in both modes
+    for mode in (o.CLIP_STANDARD, o.CLIP_AUTOMATIC):
+        C, norm = o.clip_factors(np.array([[np.nan, 4.0]]), mode, 1.0)
+        assert np.isnan(C[0]) and np.isnan(norm[0]) and np.isfinite(C[1])
 
 
 def test_standard_clipping_scale_invariance():
