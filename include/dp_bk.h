@@ -200,6 +200,23 @@ dp_status dp_clipped_grad_multi(const dp_layer* layers, int L, dp_dtype dt, int 
                                 float* const* grads, int accumulate, void* stream);
 
 /*
+ * dp_norms_multi without a workspace argument, for callers that cannot allocate device memory
+ * where they call it: code under HIP stream capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The per-tile partial sums go to a fixed 1 MiB array that is part of the library's
+ * device image (one copy per GPU, held until the process ends); the call allocates and frees
+ * nothing, on the device or on the host, and gives bit for bit the results of dp_norms_multi.
+ *   DP_ERR_WORKSPACE  the stack needs more than 1 MiB of partial sums (more than 262144 tiles
+ *                     times samples; dp_norms_multi_workspace_bytes tells) or has more than 1024
+ *                     layers: use dp_norms_multi with a workspace of your own
+ * The first call on each device looks up the array's device address (no allocation, but do it
+ * once outside stream capture).  All calls on one GPU share the array: calls that may overlap
+ * in time on one GPU (different streams, several host threads) race on it and must be
+ * serialised by the caller; calls on one stream are ordered and safe.
+ */
+dp_status dp_norms_multi_static(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out,
+                                void* stream);
+
+/*
  * dp_clipped_grad_multi with the noise of eq. (1) added in the same pass ("DP gradient" of
  * section 3 in one step): the result is what dp_clipped_grad_multi followed by dp_add_noise on
  * the same elements gives, value for value, without the second pass over the gradient.  For

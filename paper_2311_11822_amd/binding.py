@@ -42,6 +42,7 @@ _PROTOS = {
     "dp_philox_blocks": (_i, [_vp, _u64, _u64, _u64, _u64, _vp]),
     "dp_norms_multi_workspace_bytes": (_sz, [C.POINTER(dp_layer), _i, _i, _i]),
     "dp_norms_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, _vp, _sz, _vp]),
+    "dp_norms_multi_static": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, _vp]),
     "dp_clipped_grad_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp), _i, _vp]),
     "dp_clipped_grad_noise_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp),
                                         C.POINTER(_u64), _i, _u64, _u64, _f, _f, _u64, _u64, _vp]),
@@ -149,6 +150,12 @@ def dp_norms_multi(layers, dt, B, sqnorm_out, ws, stream=None) -> None:
     arr = layers if isinstance(layers, C.Array) else layer_array(layers)
     _check(lib.dp_norms_multi(arr, len(arr), dt, B, _ptr(sqnorm_out), _ptr(ws), _nbytes(ws),
                               _stream(stream)), "dp_norms_multi")
+
+
+def dp_norms_multi_static(layers, dt, B, sqnorm_out, stream=None) -> None:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    _check(lib.dp_norms_multi_static(arr, len(arr), dt, B, _ptr(sqnorm_out), _stream(stream)),
+           "dp_norms_multi_static")
 
 
 def dp_clipped_grad_multi(layers, dt, B, Cf, grads, accumulate=0, stream=None) -> None:

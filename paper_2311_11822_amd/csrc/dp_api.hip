@@ -475,6 +475,53 @@ dp_status dp_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_block
 }  // extern "C"
 
 // ---------------------------------------------------------------------------------
+// dp_norms_multi for callers that cannot allocate: the per-tile partial sums go to a fixed
+// array in the library's own device image instead of a caller-provided workspace.
+// ---------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;        // 262144 partial sums
+constexpr int kStaticMaxLayers = 1024;
+
+// One copy per device, at its own address; `scratch` itself is only a handle on the host side.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+std::atomic<void*> scratch_address[kMaxDevices];
+
+// Device address of `scratch` on the current device, resolved once per device.
+dp_status static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DP_ERR_HIP;
+  void* p = scratch_address[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DP_ERR_HIP;
+    scratch_address[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return DP_OK;
+}
+
+}  // namespace
+
+extern "C" dp_status dp_norms_multi_static(const dp_layer* layers, int L, dp_dtype dt, int B,
+                                           float* sqnorm_out, void* stream) {
+  if (!layers || L <= 0) return DP_ERR_INVALID_ARG;
+  if (L > kStaticMaxLayers) return DP_ERR_WORKSPACE;
+  const size_t need = dp_norms_multi_workspace_bytes(layers, L, dt, B);
+  if (need == 0) return DP_ERR_INVALID_ARG;
+  if (need > kStaticScratchBytes) return DP_ERR_WORKSPACE;
+  void* ws = nullptr;
+  dp_status st = static_scratch(&ws);
+  if (st != DP_OK) return st;
+  // Every partial sum that is read was written by this call's kernels first, so nothing in the
+  // array has to start at zero.
+  int64_t begin[kStaticMaxLayers];
+  int idx[3 * kStaticMaxLayers];
+  return norms_impl(layers, L, dt, B, sqnorm_out, ws, kStaticScratchBytes, static_cast<hipStream_t>(stream),
+                    begin, idx);
+}
+
+// ---------------------------------------------------------------------------------
 // Tile orders of the large-tile kernels, replayed on the host (pure functions, for tests).
 // ---------------------------------------------------------------------------------
 extern "C" {
