@@ -117,6 +117,9 @@ def measure(name, args, torch, BkPipeline, noise_pass=False):
         a, g = si.gen_layer(w, l)
         view = (lambda x: x.view(np.int16)) if w.dtype == si.BF16 else (lambda x: x)
         layers.append((torch.from_numpy(view(a)).cuda(), torch.from_numpy(view(g)).cuda()))
+        if args.zero_operands:
+            for x in layers[-1]:
+                x.zero_()
         del a, g
     pipe = BkPipeline(layers)
     off, cnt = w.noise_range()
@@ -232,6 +235,10 @@ def main():
                          "layer with thresholds R / sqrt(L), noise in a pass of its own")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
                     help="store a and g of a 16-bit workload in this type instead of the workload's own")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="diagnostic: all-zero a and g (same kernels, addresses and memory traffic, no bit "
+                         "toggling in the matrix cores); the difference to the normal run is the clock the "
+                         "device sustains under the power of real data.  Not a valid benchmark figure")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -279,7 +286,7 @@ def main():
         "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head["dtype"],
-        "data": "synthetic",
+        "data": "synthetic" if not args.zero_operands else "all-zero operands (diagnostic run, not a benchmark figure)",
         "config": {"workload": head["workload"], "clip": head["clip"], "clipping": args.clipping,
                    "R": w.R, "sigma": w.sigma, "noise_elements": head["noise_elements"], "noise": head["noise"]},
         "tflops_executed": head["tflops_executed"],
