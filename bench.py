@@ -123,14 +123,23 @@ def measure(name, args, torch, BkPipeline, noise_pass=False):
         del a, g
     pipe = BkPipeline(layers)
     off, cnt = w.noise_range()
+    passes = args.clipping == "layer-wise-passes"
     layerwise = args.clipping == "layer-wise"
     fused = not args.separate_noise and not layerwise
-    if layerwise:
+    if layerwise or passes:
         pipe.set_groups(list(range(w.L)), [w.R / w.L ** 0.5] * w.L)
 
     def step(ev=None):
         if ev:
             ev[0].record()
+        if passes:
+            # norms -> factors -> gradients (+ noise) pass by pass: one call, timed as one stage
+            pipe.layerwise_step(w.clip_mode, w.stability, w.sigma, w.noise_seed, w.noise_step, off, cnt,
+                                layers_per_pass=args.layers_per_pass)
+            if ev:
+                for e in ev[1:]:
+                    e.record()
+            return
         pipe.norms()
         if ev:
             ev[1].record()
@@ -230,9 +239,14 @@ def main():
     ap.add_argument("--separate-noise", action="store_true",
                     help="add the noise in a pass of its own (dp_add_noise) instead of in the gradient "
                          "kernels' epilogue (dp_clipped_grad_noise_multi, the faster of the two)")
-    ap.add_argument("--clipping", default="all-layer", choices=["all-layer", "layer-wise"],
+    ap.add_argument("--clipping", default="all-layer", choices=["all-layer", "layer-wise", "layer-wise-passes"],
                     help="all-layer: one clipping group (the metric's setting); layer-wise: one group per "
-                         "layer with thresholds R / sqrt(L), noise in a pass of its own")
+                         "layer with thresholds R / sqrt(L), all norms then all gradients, noise in a pass of "
+                         "its own; layer-wise-passes: the same result without book-keeping "
+                         "(dp_layerwise_clipped_grad: norms, factors, gradients and noise pass by pass; the "
+                         "stage times then hold the whole step under 'norms')")
+    ap.add_argument("--layers-per-pass", type=int, default=0,
+                    help="layer-wise-passes: layers per pass (0: the library's own pass size)")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
                     help="store a and g of a 16-bit workload in this type instead of the workload's own")
     ap.add_argument("--zero-operands", action="store_true",

@@ -263,6 +263,36 @@ dp_status dp_clipped_grad_grouped(const dp_layer* layers, int L, dp_dtype dt, in
 float dp_group_noise_threshold(const float* R, int M);
 
 /*
+ * Layer-wise clipping without book-keeping (section 3.3 (II), and the per-layer formula of the
+ * appendix on the hook-free implementation).  With one clipping group per layer, C_{l,i} depends
+ * on layer l alone, so nothing forces "all norms first, then all gradients": the stack is walked
+ * in passes of consecutive layers, and each pass runs norms -> clip factors -> weighted
+ * gradients (+ noise) before the next is touched, so a pass's a and g are still in the
+ * memory-side cache when the gradient kernels read them again.  A layer on the instantiated
+ * path (path == DP_PATH_PEREX, 16-bit storage) whose whole gradient fits one workgroup tile (up to
+ * 128 x 128, 512 x 32 or 32 x 512) is done in ONE kernel that reads a and g once: per sample it
+ * forms G_i = a_i^T g_i in registers, takes ||G_i||, C_i = clip(||G_i||; R_l) and adds C_i G_i.
+ * The result is that of dp_norms_multi + dp_clip_factors_grouped (one group per layer)
+ * + dp_clipped_grad_grouped + dp_add_noise with R = dp_group_noise_threshold(R, L):
+ *   grads[l] (+)= sum_i C[l,i] a_{l,i}^T g_{l,i} + sigma ||(R_1..R_L)||_2 z   on the shard's elements.
+ *   R            HOST, [L], each > 0 (finite when sigma > 0)
+ *   grads        HOST array of L device pointers, as dp_clipped_grad_multi
+ *   grad_offset  HOST, [L] global element offsets as dp_clipped_grad_noise_multi (may be NULL when
+ *                sigma == 0 or shard_count == 0)
+ *   sqnorm_out, C_out   device, [L, B] fp32, overwritten
+ *   ws           device scratch >= dp_layerwise_workspace_bytes(...), 16-byte aligned
+ *   layers_per_pass   0: a pass ends once it holds 128 MiB of a and g and 1024 gradient tiles;
+ *                     > 0: that many layers per pass
+ */
+size_t dp_layerwise_workspace_bytes(const dp_layer* layers, int L, dp_dtype dt, int B);
+dp_status dp_layerwise_clipped_grad(const dp_layer* layers, int L, dp_dtype dt, int B, const float* R,
+                                    dp_clip_mode mode, float stability, float* const* grads,
+                                    const uint64_t* grad_offset, int accumulate, uint64_t shard_offset,
+                                    uint64_t shard_count, float sigma, uint64_t seed, uint64_t step,
+                                    float* sqnorm_out, float* C_out, void* ws, size_t ws_bytes,
+                                    int layers_per_pass, void* stream);
+
+/*
  * Bias gradients (appendix A.1, last paragraph): the per-sample bias gradient is 1^T dL/ds_i, the
  * sum of sample i's T rows of g; its norm is taken by instantiation.
  * dp_bias_norm:  colsum[i, k] = sum_t g[i, t, k]  and  sqnorm_out[i] = sum_k colsum[i, k]^2.

@@ -52,6 +52,9 @@ _PROTOS = {
     "dp_group_noise_threshold": (_f, [C.POINTER(_f), _i]),
     "dp_bias_norm": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp]),
     "dp_clipped_bias_grad": (_i, [_vp, _i, _i, _vp, _vp, _i, _vp]),
+    "dp_layerwise_workspace_bytes": (_sz, [C.POINTER(dp_layer), _i, _i, _i]),
+    "dp_layerwise_clipped_grad": (_i, [C.POINTER(dp_layer), _i, _i, _i, C.POINTER(_f), _i, _f, C.POINTER(_vp),
+                                      C.POINTER(_u64), _i, _u64, _u64, _f, _u64, _u64, _vp, _vp, _vp, _sz, _i, _vp]),
     "dp_clipped_grad_tile_order": (C.c_int64, [_i, _i, _vp, _vp, C.c_int64]),
     "dp_ghost_tile_order": (C.c_int64, [_i, _i, _vp, _vp, _vp, _vp, C.c_int64]),
 }
@@ -210,6 +213,25 @@ def dp_bias_norm(g, dt, B, T, d_out, colsum, sqnorm_out, stream=None) -> None:
 def dp_clipped_bias_grad(colsum, B, d_out, Cf, grad_b, accumulate=0, stream=None) -> None:
     _check(lib.dp_clipped_bias_grad(_ptr(colsum), B, d_out, _ptr(Cf), _ptr(grad_b), accumulate, _stream(stream)),
            "dp_clipped_bias_grad")
+
+
+def dp_layerwise_workspace_bytes(layers, dt, B) -> int:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    return lib.dp_layerwise_workspace_bytes(arr, len(arr), dt, B)
+
+
+def dp_layerwise_clipped_grad(layers, dt, B, R, mode, stability, grads, grad_offset, accumulate, shard_offset,
+                              shard_count, sigma, seed, step, sqnorm_out, C_out, ws, layers_per_pass=0,
+                              stream=None) -> None:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    gp = grads if isinstance(grads, C.Array) else (C.c_void_p * len(grads))(*[_ptr(x) for x in grads])
+    offs = None
+    if grad_offset is not None:
+        offs = grad_offset if isinstance(grad_offset, C.Array) else (C.c_uint64 * len(grad_offset))(*grad_offset)
+    _check(lib.dp_layerwise_clipped_grad(arr, len(arr), dt, B, _f32(R), mode, stability, gp, offs, accumulate,
+                                         shard_offset, shard_count, sigma, seed, step, _ptr(sqnorm_out),
+                                         _ptr(C_out), _ptr(ws), _nbytes(ws), layers_per_pass, _stream(stream)),
+           "dp_layerwise_clipped_grad")
 
 
 def dp_clipped_grad_tile_order(d_in: int, d_out: int):

@@ -46,7 +46,7 @@ enum NormKernel { kGhostBig = 0, kGhostSmall = 1, kPerex = 2 };
 
 dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, int n_which,
                         const int64_t* part_begin, dp_dtype dt, int B, float* partials,
-                        float* sqnorm_out, hipStream_t s) {
+                        float* sqnorm_out, hipStream_t s, const int* row_of) {
   // A tile's length is the contraction it runs over (d_in + d_out for the ghost norm, T for the
   // instantiated one).  Longest first: workgroups are handed out in order, so the short tiles
   // fill the end of the launch.  Each layer writes its own workspace slots and sqnorm row, so
@@ -79,7 +79,7 @@ dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, i
       gl.d_out = layers[l].d_out;
       gl.path = kernel == kPerex ? DP_PATH_PEREX : DP_PATH_GHOST;
       gl.tile_begin = (int)blocks;
-      gl.sq_index = l;
+      gl.sq_index = row_of ? row_of[l] : l;
       gl.part_begin = (int)part_begin[l];
       gl.tiles_per_sample = tiles_per_sample(gl.path, layers[l]);
       gl.c_off = 0;
@@ -111,9 +111,10 @@ int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, int64_t* b
 }
 
 // begin: room for L values; idx: room for 3 L values (the layers of each kernel).  The caller
-// provides both so that this function never touches the heap.
+// provides both so that this function never touches the heap.  row_of (or nullptr): layer l's
+// squared norms go to row row_of[l] of sqnorm_out instead of row l.
 dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
-                     size_t ws_bytes, hipStream_t s, int64_t* begin, int* idx) {
+                     size_t ws_bytes, hipStream_t s, int64_t* begin, int* idx, const int* row_of = nullptr) {
   if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!sqnorm_out) return DP_ERR_INVALID_ARG;
   const int64_t slots = norm_slots(layers, L, dt, B, begin);
@@ -134,7 +135,7 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
       const dp_layer& ly = layers[l];
       const float* a = static_cast<const float*>(ly.a);
       const float* g = static_cast<const float*>(ly.g);
-      float* out = sqnorm_out + (size_t)l * B;
+      float* out = sqnorm_out + (size_t)(row_of ? row_of[l] : l) * B;
       dp_status st = ly.path == DP_PATH_GHOST ? launch_ghost_f32(a, g, B, ly.T, ly.d_in, ly.d_out, out, s)
                                               : launch_perex_f32(a, g, B, ly.T, ly.d_in, ly.d_out, out, s);
       if (st != DP_OK) return st;
@@ -151,18 +152,19 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
   }
   float* partials = static_cast<float*>(ws);
   for (int k = 0; k < 3; ++k) {
-    dp_status st = run_norm_path((NormKernel)k, layers, list[k], count[k], begin, dt, B, partials, sqnorm_out, s);
+    dp_status st = run_norm_path((NormKernel)k, layers, list[k], count[k], begin, dt, B, partials, sqnorm_out, s,
+                                 row_of);
     if (st != DP_OK) return st;
   }
   return DP_OK;
 }
 
 dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
-                     size_t ws_bytes, hipStream_t s) {
+                     size_t ws_bytes, hipStream_t s, const int* row_of = nullptr) {
   if (!layers || L <= 0) return DP_ERR_INVALID_ARG;
   std::vector<int64_t> begin(L);
   std::vector<int> idx(3 * (size_t)L);
-  return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, s, begin.data(), idx.data());
+  return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, s, begin.data(), idx.data(), row_of);
 }
 
 dp_status single_norm(dp_path path, const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
@@ -470,6 +472,205 @@ dp_status dp_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_block
   if (n_blocks == 0) return DP_OK;
   if (first_block + n_blocks < first_block) return DP_ERR_INVALID_ARG;
   return launch_philox_blocks(out, first_block, n_blocks, seed, step, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"
+
+
+// ---------------------------------------------------------------------------------
+// Layer-wise clipping without book-keeping (section 3.3 (II); appendix on the hook-free form).
+// ---------------------------------------------------------------------------------
+namespace {
+
+// A pass ends once its a and g exceed half the memory-side cache, but not before it holds enough
+// gradient tiles for four rounds of workgroups: launches that leave compute units idle cost more
+// than re-reading a and g from memory (measured on a GPT-2-small stack: passes of 4 layers
+// 2.3 ms, 8 layers 1.39 ms, 16 layers 1.38 ms, all norms then all gradients 1.31 ms).
+constexpr int64_t kPassBytes = (int64_t)128 << 20;
+constexpr int64_t kPassTiles = 1024;
+
+// Which layers the one-pass kernel takes, and its sample chunks.
+struct FusedPlan {
+  std::vector<int> shape;        // per layer: shape class or -1
+  int n_fused = 0;
+  int chunks = 1;                // sample chunks per fused layer
+  int64_t floats = 0;            // partial sums of all fused layers
+};
+
+FusedPlan plan_fused(const dp_layer* layers, int L, dp_dtype dt, int B) {
+  FusedPlan fp;
+  fp.shape.assign(L, -1);
+  if (dt == DP_F32) return fp;
+  for (int l = 0; l < L; ++l)
+    if (layers[l].path == DP_PATH_PEREX) {
+      fp.shape[l] = layerwise_fused_shape(layers[l].d_in, layers[l].d_out);
+      fp.n_fused += fp.shape[l] >= 0;
+    }
+  if (fp.n_fused == 0) return fp;
+  // enough workgroups to fill the 256 compute units when the batch allows
+  const int want = std::min(B, std::max(1, 256 / fp.n_fused));
+  const int per = (B + want - 1) / want;
+  fp.chunks = (B + per - 1) / per;
+  for (int l = 0; l < L; ++l)
+    if (fp.shape[l] >= 0) fp.floats += (int64_t)fp.chunks * layers[l].d_in * layers[l].d_out;
+  return fp;
+}
+
+size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+}  // namespace
+
+extern "C" {
+
+size_t dp_layerwise_workspace_bytes(const dp_layer* layers, int L, dp_dtype dt, int B) {
+  const size_t norms = dp_norms_multi_workspace_bytes(layers, L, dt, B);
+  if (norms == 0) return 0;
+  const FusedPlan fp = plan_fused(layers, L, dt, B);
+  if (fp.floats > INT32_MAX) return 0;
+  return align16(norms) + (size_t)fp.floats * sizeof(float);
+}
+
+dp_status dp_layerwise_clipped_grad(const dp_layer* layers, int L, dp_dtype dt, int B, const float* R,
+                                    dp_clip_mode mode, float stability, float* const* grads,
+                                    const uint64_t* grad_offset, int accumulate, uint64_t shard_offset,
+                                    uint64_t shard_count, float sigma, uint64_t seed, uint64_t step,
+                                    float* sqnorm_out, float* C_out, void* ws, size_t ws_bytes,
+                                    int layers_per_pass, void* stream) {
+  if (!dtype_ok(dt) || !layers || !R || !grads || !sqnorm_out || !C_out || L <= 0 || B <= 0) return DP_ERR_INVALID_ARG;
+  if (mode != DP_CLIP_STANDARD && mode != DP_CLIP_AUTOMATIC) return DP_ERR_INVALID_ARG;
+  if (!(stability >= 0.f) || isinf(stability)) return DP_ERR_INVALID_ARG;
+  if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
+  if (layers_per_pass < 0 || (int64_t)L * B > INT32_MAX) return DP_ERR_INVALID_ARG;
+  if (!(sigma >= 0.f) || isinf(sigma)) return DP_ERR_INVALID_ARG;
+  if (shard_offset + shard_count < shard_offset) return DP_ERR_INVALID_ARG;
+  double r2 = 0.0;
+  for (int l = 0; l < L; ++l) {
+    if (!(R[l] > 0.f)) return DP_ERR_INVALID_ARG;
+    r2 += (double)R[l] * R[l];
+    if (!dims_ok(dt, B, layers[l].T, layers[l].d_in, layers[l].d_out)) return DP_ERR_INVALID_ARG;
+    if (layers[l].path != DP_PATH_GHOST && layers[l].path != DP_PATH_PEREX) return DP_ERR_INVALID_ARG;
+    dp_status st = check_layer_ptrs(layers[l].a, layers[l].g);
+    if (st != DP_OK) return st;
+    if (!grads[l] || !aligned16(grads[l])) return DP_ERR_INVALID_ARG;
+  }
+  const bool noisy = sigma > 0.f && shard_count > 0;
+  const float stddev = noisy ? (float)(sigma * sqrt(r2)) : 0.f;          // eq. (1): sigma ||(R_1..R_L)||
+  if (noisy) {
+    if (!grad_offset || isinf(stddev)) return DP_ERR_INVALID_ARG;
+    for (int l = 0; l < L; ++l) {
+      const uint64_t n = (uint64_t)layers[l].d_in * (uint64_t)layers[l].d_out;
+      if (grad_offset[l] + n < grad_offset[l]) return DP_ERR_INVALID_ARG;
+    }
+  }
+  const size_t need = dp_layerwise_workspace_bytes(layers, L, dt, B);
+  if (need == 0) return DP_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < need) return DP_ERR_WORKSPACE;
+  if (!aligned16(ws)) return DP_ERR_INVALID_ARG;
+  const FusedPlan fp = plan_fused(layers, L, dt, B);
+  float* fused_partial = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) +
+                                                  align16(dp_norms_multi_workspace_bytes(layers, L, dt, B)));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  NoiseArgs na = {};
+  na.stddev = stddev;
+  na.step_lo = (uint32_t)step;
+  na.step_hi = (uint32_t)(step >> 32);
+  na.lo = shard_offset;
+  na.hi = shard_offset + shard_count;
+  na.rk = make_round_keys(seed);
+
+  int64_t fused_off = 0;
+  for (int l0 = 0; l0 < L;) {
+    // one pass: consecutive layers whose a and g stay in the memory-side cache between the norm
+    // kernels and the gradient kernels (or layers_per_pass of them when the caller says so)
+    int l1 = l0;
+    int64_t bytes = 0, tiles = 0;
+    const int64_t esize = dt == DP_F32 ? 4 : 2;
+    while (l1 < L) {
+      const bool small = fp.shape[l1] >= 0;
+      const int64_t lb = small ? 0 : (int64_t)B * layers[l1].T * ((int64_t)layers[l1].d_in + layers[l1].d_out) * esize;
+      if (l1 > l0 && (layers_per_pass > 0 ? l1 - l0 >= layers_per_pass
+                                          : bytes + lb > kPassBytes && tiles >= kPassTiles)) break;
+      bytes += lb;
+      tiles += small ? 0 : clipped_grad_big_tiles(layers[l1].d_in, layers[l1].d_out);
+      ++l1;
+    }
+    // (1) layers that fit one workgroup tile: norm, clip factor and weighted sum in one kernel
+    for (int shape = 0; shape < 3; ++shape) {
+      int l = l0;
+      while (l < l1) {
+        GroupArgs ga;
+        ga.B = B;
+        ga.accumulate = accumulate;
+        ga.f16 = dt == DP_F16;
+        ga.n_layers = 0;
+        float Rg[kMaxGroup];
+        int blocks = 0;
+        for (; l < l1 && ga.n_layers < kMaxGroup; ++l) {
+          if (fp.shape[l] != shape) continue;
+          GroupLayer& gl = ga.layer[ga.n_layers];
+          gl.a = layers[l].a;
+          gl.g = layers[l].g;
+          gl.out = grads[l];
+          gl.T = layers[l].T;
+          gl.d_in = layers[l].d_in;
+          gl.d_out = layers[l].d_out;
+          gl.path = DP_PATH_PEREX;
+          gl.tile_begin = blocks;
+          gl.sq_index = l;
+          gl.part_begin = (int)fused_off;
+          gl.tiles_per_sample = fp.chunks;
+          gl.c_off = 0;
+          Rg[ga.n_layers] = R[l];
+          na.layer_off[ga.n_layers] = noisy ? grad_offset[l] : 0;
+          fused_off += (int64_t)fp.chunks * gl.d_in * gl.d_out;
+          blocks += fp.chunks;
+          ++ga.n_layers;
+        }
+        if (ga.n_layers == 0) break;
+        ga.total_blocks = blocks;
+        dp_status st = launch_layerwise_fused(shape, ga, Rg, (int)mode, stability, fused_partial, sqnorm_out, C_out, s);
+        if (st != DP_OK) return st;
+        st = launch_layerwise_reduce(ga, fused_partial, na, s);
+        if (st != DP_OK) return st;
+      }
+    }
+    // (2) the other layers of the pass: norms, clip factors, weighted gradients
+    std::vector<dp_layer> sub;
+    std::vector<int> row, c_off;
+    std::vector<float*> sub_grads;
+    std::vector<uint64_t> sub_off;
+    for (int l = l0; l < l1; ++l)
+      if (fp.shape[l] < 0) {
+        sub.push_back(layers[l]);
+        row.push_back(l);
+        c_off.push_back(l * B);
+        sub_grads.push_back(grads[l]);
+        sub_off.push_back(noisy ? grad_offset[l] : 0);
+      }
+    if (!sub.empty()) {
+      const int n = (int)sub.size();
+      dp_status st = norms_impl(sub.data(), n, dt, B, sqnorm_out, ws, ws_bytes, s, row.data());
+      if (st != DP_OK) return st;
+      std::vector<int32_t> begin(l1 - l0 + 1);
+      for (int l = l0; l <= l1; ++l) begin[l - l0] = l;
+      st = launch_clip_factors_grouped(sqnorm_out, B, begin.data(), l1 - l0, R + l0, (int)mode, stability,
+                                       C_out + (size_t)l0 * B, nullptr, s);
+      if (st != DP_OK) return st;
+      NoiseSpec spec;
+      spec.grad_offset = sub_off.data();
+      spec.lo = shard_offset;
+      spec.hi = shard_offset + shard_count;
+      spec.stddev = stddev;
+      spec.seed = seed;
+      spec.step = step;
+      st = clipped_grad_impl(sub.data(), n, dt, B, C_out, c_off.data(), sub_grads.data(), accumulate, stream,
+                             noisy ? &spec : nullptr);
+      if (st != DP_OK) return st;
+    }
+    l0 = l1;
+  }
+  return DP_OK;
 }
 
 }  // extern "C"

@@ -150,4 +150,14 @@ bool clipped_grad_big_supports(int T, int d, int p);
 dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, const NoiseArgs* noise,
                                         hipStream_t s);
 
+// Layer-wise clipping in one pass for layers that fit one workgroup tile (layerwise.hip).
+// Shape class of a d x p layer (0: up to 128 x 128, 1: up to 512 x 32, 2: up to 32 x 512), or -1.
+int layerwise_fused_shape(int d, int p);
+// ga.layer[j]: tile_begin = first workgroup, tiles_per_sample = sample chunks, part_begin = float
+// offset of the layer's [chunks][d * p] sums in `partial`, sq_index = row of sqnorm / C_out.
+dp_status launch_layerwise_fused(int shape, const GroupArgs& ga, const float* R, int mode, float stability,
+                                 float* partial, float* sqnorm, float* C_out, hipStream_t s);
+// ga.layer[j].out (+)= the layer's chunks added in order (+ noise when na.stddev != 0).
+dp_status launch_layerwise_reduce(const GroupArgs& ga, const float* partial, const NoiseArgs& na, hipStream_t s);
+
 }  // namespace dpbk

@@ -87,6 +87,20 @@ class BkPipeline:
     def noise_grouped(self, sigma, seed, step, offset, count, stream=None):
         self.noise(sigma, dp.dp_group_noise_threshold(self.group_R), seed, step, offset, count, stream)
 
+    def layerwise_step(self, mode, stability, sigma, seed, step, offset, count, layers_per_pass=0,
+                       accumulate=0, stream=None):
+        """Layer-wise clipping (groups set with set_groups: one group per layer) without
+        book-keeping: pass by pass norms -> factors -> gradients (+ noise), small layers in one kernel."""
+        assert self.group_of_layer == list(range(self.L))
+        if getattr(self, "ws_layerwise", None) is None:
+            n = dp.dp_layerwise_workspace_bytes(self.desc, self.dt, self.B)
+            if n == 0:
+                raise dp.DpError(dp.DP_ERR_INVALID_ARG, "dp_layerwise_workspace_bytes")
+            self.ws_layerwise = torch.empty(n, dtype=torch.uint8, device=self.device)
+        dp.dp_layerwise_clipped_grad(self.desc, self.dt, self.B, self.group_R, mode, stability, self.grad_ptrs,
+                                     self.grad_offsets, accumulate, offset, count, sigma, seed, step,
+                                     self.sqnorm, self.C_groups, self.ws_layerwise, layers_per_pass, stream)
+
     def step(self, mode, R, sigma, stability, seed, step, offset, count, stream=None, fused=True):
         self.norms(stream)
         self.clip(mode, R, stability, stream)

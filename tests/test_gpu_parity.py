@@ -769,6 +769,118 @@ def test_pipeline_layerwise_step(dp, Pipe):
 
 
 # ----------------------------------------------------------------------------
+# layer-wise clipping without book-keeping (dp_layerwise_clipped_grad)
+# ----------------------------------------------------------------------------
+
+LAYERWISE_STACK = [(72, 24), (128, 128), (392, 24), (24, 392), (136, 264), (392, 520), (16, 8), (104, 128)]
+
+
+@pytest.mark.parametrize("dtype", HALF_TYPES)
+@pytest.mark.parametrize("mode,stability", [(0, 0.01), (1, 0.01), (1, 0.0)])
+def test_layerwise_without_book_keeping(dp, Pipe, dtype, mode, stability):
+    # Small layers on the instantiated path (the first four and the last two fit one workgroup
+    # tile: norm, factor and weighted sum in one kernel), a larger one on it, and one on the
+    # ghost path; five samples so that the sample chunks of the one-pass kernel are uneven.
+    dims, B, T = LAYERWISE_STACK, 5, 200
+    w = si.small_workload("lw1", dtype, B, T, dims)
+    layers = gen(w)
+    # per-sample scales so that standard clipping takes both branches in most layers
+    scale = np.array([1e-3, 1.0, 3e-2, 10.0, 0.3], dtype=np.float32)
+    if dtype == si.BF16:
+        layers = [(a, si.f32_to_bf16_bits(si.bf16_bits_to_f32(g) * scale[:, None, None])) for a, g in layers]
+    else:
+        layers = [(a, (g.astype(np.float32) * scale[:, None, None]).astype(np.float16)) for a, g in layers]
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    L = len(dims)
+    R = [0.05, 0.5, 0.02, 0.1, 0.3, 1.0, 0.01, 0.2]
+    sigma, seed, step = 0.6, 21, 4
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    assert pipe.paths == [o.choose_path(T, d, p) for d, p in dims] == [1, 1, 1, 1, 1, 0, 1, 1]
+    pipe.set_groups(list(range(L)), R)
+    psi = pipe.psi
+    ref = o.private_gradient_grouped(l64, list(range(L)), R, mode, 0.0, stability, seed, step, 0, 0)
+    pipe.flat.fill_(9.0)
+    pipe.layerwise_step(mode, stability, 0.0, seed, step, 0, psi)
+    assert rel(host(pipe.sqnorm), ref["sqnorm"]) <= TOL_BF16_NORM
+    assert rel(host(pipe.C_groups), ref["C"]) <= TOL_BF16_NORM
+    if mode == 0:
+        assert (ref["C"] == 1.0).sum() >= L and (ref["C"] < 1.0).sum() >= L
+        assert np.array_equal(host(pipe.C_groups) == 1.0, ref["C"] == 1.0)
+    # the gradient against the oracle's definition with the weights the kernels used
+    Cg = host(pipe.C_groups).astype(np.float64)
+    clean = host(pipe.flat).copy()
+    for l, (a, g) in enumerate(l64):
+        assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, Cg[l])) <= 1e-5, l
+    assert frob(clean, ref["flat"]) <= 2 * TOL_BF16_NORM      # weights differ by the norms' rounding
+    # the same bits whatever the pass size
+    for per_pass in (1, 3):
+        pipe.flat.fill_(-1.0)
+        pipe.layerwise_step(mode, stability, 0.0, seed, step, 0, psi, layers_per_pass=per_pass)
+        np.testing.assert_array_equal(host(pipe.flat), clean)
+    # the layers the grouped kernels compute give the bits of the two-pass sequence
+    pipe.norms()
+    pipe.clip_grouped(mode, stability)
+    pipe.flat.fill_(3.0)
+    pipe.grad_grouped()
+    for l in (4, 5):
+        np.testing.assert_array_equal(host(pipe.grads[l]).reshape(-1), clean[sum(d * p for d, p in dims[:l]):][:dims[l][0] * dims[l][1]])
+    # accumulate, and noise of level sigma ||R||_2 on a shard that starts and ends inside layers
+    lo, cnt = 1000, psi - 1500
+    pipe.flat.copy_(torch.from_numpy(clean).cuda())
+    pipe.layerwise_step(mode, stability, sigma, seed, step, lo, cnt, accumulate=1)
+    got = host(pipe.flat).astype(np.float64)
+    z = np.zeros(psi)
+    z[lo:lo + cnt] = o.normals(seed, step, lo, cnt)
+    std = o.group_noise_std(sigma, R)
+    want = 2.0 * clean.astype(np.float64) + std * z
+    assert np.all(np.abs(got - want) <= 2e-5 * std * np.maximum(1.0, np.abs(z)) + 1e-5 * np.abs(clean))
+    assert np.array_equal(got[:lo], 2.0 * clean[:lo].astype(np.float64))
+
+
+def test_layerwise_without_book_keeping_fp32(dp, Pipe):
+    dims, B, T = [(4, 8), (8, 4), (4, 12)], 4, 6
+    w = si.small_workload("lw32", si.F32, B, T, dims, g_std=1.0)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    R = [0.5, 2.0, 1e3]
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    pipe.set_groups([0, 1, 2], R)
+    pipe.layerwise_step(dp.DP_CLIP_STANDARD, 0.01, 0.4, 3, 1, 0, pipe.psi)
+    ref = o.private_gradient_grouped(l64, [0, 1, 2], R, o.CLIP_STANDARD, 0.4, 0.01, 3, 1, 0, pipe.psi)
+    assert rel(host(pipe.C_groups), ref["C"]) <= TOL_F32
+    np.testing.assert_allclose(host(pipe.flat), ref["flat"], rtol=TOL_F32, atol=2e-5)
+
+
+def test_layerwise_argument_errors(dp):
+    import ctypes
+    x = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    p = x.data_ptr()
+    lib, INV = dp.lib, dp.DP_ERR_INVALID_ARG
+    arr = dp.layer_array([(p, p, 8, 8, 8, 1)])
+    gp = (ctypes.c_void_p * 1)(p + 8192)
+    offs = (ctypes.c_uint64 * 1)(0)
+    R = (ctypes.c_float * 1)(1.0)
+    bad_R = (ctypes.c_float * 1)(0.0)
+    n = dp.dp_layerwise_workspace_bytes(arr, dp.DP_BF16, 1)
+    assert n > 0
+    call = lambda *a: lib.dp_layerwise_clipped_grad(*a)
+    ok = [arr, 1, 1, 1, R, 0, 0.01, gp, offs, 0, 0, 16, 1.0, 0, 0, p, p + 4096, p + 1024, n, 0, None]
+    def with_(i, v):
+        a = list(ok)
+        a[i] = v
+        return a
+    assert call(*with_(4, bad_R)) == INV
+    assert call(*with_(5, 2)) == INV
+    assert call(*with_(8, None)) == INV                   # noise asked for, no offsets
+    assert call(*with_(12, -1.0)) == INV
+    assert call(*with_(15, None)) == INV
+    assert call(*with_(18, 0)) == dp.DP_ERR_WORKSPACE
+    assert call(*with_(19, -1)) == INV
+    torch.cuda.synchronize()
+    assert not host(x).any()
+
+
+# ----------------------------------------------------------------------------
 # gradient + noise in one pass (dp_clipped_grad_noise_multi)
 # ----------------------------------------------------------------------------
 
