@@ -263,6 +263,31 @@ dp_status dp_clipped_grad_grouped(const dp_layer* layers, int L, dp_dtype dt, in
 float dp_group_noise_threshold(const float* R, int M);
 
 /*
+ * Book-keeping for layers on the instantiated path (appendix A.2 applied to the left side of
+ * appendix A.1's equation): the norm kernel already forms every per-sample gradient
+ * G_{l,i} = a_{l,i}^T g_{l,i}; when the caller gives it room, it keeps them, and the
+ * clip-weighted gradient is then sum_i C_i G_{l,i} -- a stream over B arrays of d_in * d_out floats
+ * instead of a second contraction over the T tokens of a and g.  The rule that puts a layer on
+ * this path (2 T^2 > d_in * d_out) also makes the kept gradients smaller than the layer's two
+ * Gram matrices would be.
+ * dp_norms_multi_keep: dp_norms_multi, and for every layer with kept[l] != NULL also
+ *   kept[l][i, j, k] = sum_t a[i,t,j] g[i,t,k]   (fp32, [B, d_in, d_out], overwritten).
+ *   kept   HOST array of L device pointers (16-byte aligned) or NULLs; NULL array = keep nothing.
+ *          A non-NULL entry needs path == DP_PATH_PEREX and 16-bit storage (else
+ *          DP_ERR_INVALID_ARG / DP_ERR_UNSUPPORTED).
+ * dp_clipped_grad_kept_multi: dp_clipped_grad_noise_multi, with the layers that have kept[l] != NULL
+ *   computed from kept[l] (a and g of those layers are not read; their descriptors still give
+ *   the shapes).  Samples are added in index order in fp32; samples with C[i] == 0 are not read.
+ *   grad_offset may be NULL when sigma == 0 or shard_count == 0.
+ */
+dp_status dp_norms_multi_keep(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out,
+                              float* const* kept, void* ws, size_t ws_bytes, void* stream);
+dp_status dp_clipped_grad_kept_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                     float* const* kept, float* const* grads, const uint64_t* grad_offset,
+                                     int accumulate, uint64_t shard_offset, uint64_t shard_count, float sigma,
+                                     float R, uint64_t seed, uint64_t step, void* stream);
+
+/*
  * Layer-wise clipping without book-keeping (section 3.3 (II), and the per-layer formula of the
  * appendix on the hook-free implementation).  With one clipping group per layer, C_{l,i} depends
  * on layer l alone, so nothing forces "all norms first, then all gradients": the stack is walked

@@ -52,6 +52,9 @@ _PROTOS = {
     "dp_group_noise_threshold": (_f, [C.POINTER(_f), _i]),
     "dp_bias_norm": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp]),
     "dp_clipped_bias_grad": (_i, [_vp, _i, _i, _vp, _vp, _i, _vp]),
+    "dp_norms_multi_keep": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp), _vp, _sz, _vp]),
+    "dp_clipped_grad_kept_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp), C.POINTER(_vp),
+                                       C.POINTER(_u64), _i, _u64, _u64, _f, _f, _u64, _u64, _vp]),
     "dp_layerwise_workspace_bytes": (_sz, [C.POINTER(dp_layer), _i, _i, _i]),
     "dp_layerwise_clipped_grad": (_i, [C.POINTER(dp_layer), _i, _i, _i, C.POINTER(_f), _i, _f, C.POINTER(_vp),
                                       C.POINTER(_u64), _i, _u64, _u64, _f, _u64, _u64, _vp, _vp, _vp, _sz, _i, _vp]),
@@ -213,6 +216,30 @@ def dp_bias_norm(g, dt, B, T, d_out, colsum, sqnorm_out, stream=None) -> None:
 def dp_clipped_bias_grad(colsum, B, d_out, Cf, grad_b, accumulate=0, stream=None) -> None:
     _check(lib.dp_clipped_bias_grad(_ptr(colsum), B, d_out, _ptr(Cf), _ptr(grad_b), accumulate, _stream(stream)),
            "dp_clipped_bias_grad")
+
+
+def _ptr_array(xs):
+    """HOST array of device pointers; None entries become NULL."""
+    if isinstance(xs, C.Array):
+        return xs
+    return (C.c_void_p * len(xs))(*[_ptr(x) for x in xs])
+
+
+def dp_norms_multi_keep(layers, dt, B, sqnorm_out, kept, ws, stream=None) -> None:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    _check(lib.dp_norms_multi_keep(arr, len(arr), dt, B, _ptr(sqnorm_out), _ptr_array(kept) if kept is not None else None,
+                                   _ptr(ws), _nbytes(ws), _stream(stream)), "dp_norms_multi_keep")
+
+
+def dp_clipped_grad_kept_multi(layers, dt, B, Cf, kept, grads, grad_offset, accumulate, shard_offset, shard_count,
+                               sigma, R, seed, step, stream=None) -> None:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    offs = None
+    if grad_offset is not None:
+        offs = grad_offset if isinstance(grad_offset, C.Array) else (C.c_uint64 * len(grad_offset))(*grad_offset)
+    _check(lib.dp_clipped_grad_kept_multi(arr, len(arr), dt, B, _ptr(Cf), _ptr_array(kept) if kept is not None else None,
+                                          _ptr_array(grads), offs, accumulate, shard_offset, shard_count, sigma, R,
+                                          seed, step, _stream(stream)), "dp_clipped_grad_kept_multi")
 
 
 def dp_layerwise_workspace_bytes(layers, dt, B) -> int:

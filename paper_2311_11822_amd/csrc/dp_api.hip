@@ -46,7 +46,7 @@ enum NormKernel { kGhostBig = 0, kGhostSmall = 1, kPerex = 2 };
 
 dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, int n_which,
                         const int64_t* part_begin, dp_dtype dt, int B, float* partials,
-                        float* sqnorm_out, hipStream_t s, const int* row_of) {
+                        float* sqnorm_out, hipStream_t s, const int* row_of, float* const* kept) {
   // A tile's length is the contraction it runs over (d_in + d_out for the ghost norm, T for the
   // instantiated one).  Longest first: workgroups are handed out in order, so the short tiles
   // fill the end of the launch.  Each layer writes its own workspace slots and sqnorm row, so
@@ -73,7 +73,7 @@ dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, i
       GroupLayer& gl = ga.layer[j];
       gl.a = layers[l].a;
       gl.g = layers[l].g;
-      gl.out = nullptr;
+      gl.out = kernel == kPerex && kept ? kept[l] : nullptr;
       gl.T = layers[l].T;
       gl.d_in = layers[l].d_in;
       gl.d_out = layers[l].d_out;
@@ -114,7 +114,8 @@ int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, int64_t* b
 // provides both so that this function never touches the heap.  row_of (or nullptr): layer l's
 // squared norms go to row row_of[l] of sqnorm_out instead of row l.
 dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
-                     size_t ws_bytes, hipStream_t s, int64_t* begin, int* idx, const int* row_of = nullptr) {
+                     size_t ws_bytes, hipStream_t s, int64_t* begin, int* idx, const int* row_of = nullptr,
+                     float* const* kept = nullptr) {
   if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!sqnorm_out) return DP_ERR_INVALID_ARG;
   const int64_t slots = norm_slots(layers, L, dt, B, begin);
@@ -153,18 +154,18 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
   float* partials = static_cast<float*>(ws);
   for (int k = 0; k < 3; ++k) {
     dp_status st = run_norm_path((NormKernel)k, layers, list[k], count[k], begin, dt, B, partials, sqnorm_out, s,
-                                 row_of);
+                                 row_of, kept);
     if (st != DP_OK) return st;
   }
   return DP_OK;
 }
 
 dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
-                     size_t ws_bytes, hipStream_t s, const int* row_of = nullptr) {
+                     size_t ws_bytes, hipStream_t s, const int* row_of = nullptr, float* const* kept = nullptr) {
   if (!layers || L <= 0) return DP_ERR_INVALID_ARG;
   std::vector<int64_t> begin(L);
   std::vector<int> idx(3 * (size_t)L);
-  return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, s, begin.data(), idx.data(), row_of);
+  return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, s, begin.data(), idx.data(), row_of, kept);
 }
 
 dp_status single_norm(dp_path path, const void* a, const void* g, dp_dtype dt, int B, int T, int d_in,
@@ -478,6 +479,136 @@ dp_status dp_philox_blocks(uint32_t* out, uint64_t first_block, uint64_t n_block
 
 
 // ---------------------------------------------------------------------------------
+// Instantiated layers with their per-sample gradients kept between the two halves.
+// ---------------------------------------------------------------------------------
+namespace {
+
+// kept[l] may be given only for 16-bit layers on the instantiated path, 16-byte aligned.
+dp_status check_kept(const dp_layer* layers, int L, dp_dtype dt, float* const* kept) {
+  if (!kept) return DP_OK;
+  for (int l = 0; l < L; ++l) {
+    if (!kept[l]) continue;
+    if (dt == DP_F32) return DP_ERR_UNSUPPORTED;
+    if (layers[l].path != DP_PATH_PEREX || !aligned16(kept[l])) return DP_ERR_INVALID_ARG;
+    if ((int64_t)layers[l].d_in * layers[l].d_out > INT32_MAX) return DP_ERR_INVALID_ARG;
+  }
+  return DP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+dp_status dp_norms_multi_keep(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out,
+                              float* const* kept, void* ws, size_t ws_bytes, void* stream) {
+  if (!layers || L <= 0) return DP_ERR_INVALID_ARG;
+  for (int l = 0; l < L; ++l)
+    if (layers[l].path != DP_PATH_GHOST && layers[l].path != DP_PATH_PEREX) return DP_ERR_INVALID_ARG;
+  dp_status st = check_kept(layers, L, dt, kept);
+  if (st != DP_OK) return st;
+  return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, static_cast<hipStream_t>(stream), nullptr, kept);
+}
+
+dp_status dp_clipped_grad_kept_multi(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                     float* const* kept, float* const* grads, const uint64_t* grad_offset,
+                                     int accumulate, uint64_t shard_offset, uint64_t shard_count, float sigma,
+                                     float R, uint64_t seed, uint64_t step, void* stream) {
+  if (!layers || !grads || !C || L <= 0 || B <= 0 || !dtype_ok(dt)) return DP_ERR_INVALID_ARG;
+  if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
+  if (!(sigma >= 0.f) || isinf(sigma) || !(R > 0.f)) return DP_ERR_INVALID_ARG;
+  if (shard_offset + shard_count < shard_offset) return DP_ERR_INVALID_ARG;
+  const bool noisy = sigma > 0.f && shard_count > 0;
+  if (noisy && (isinf(R) || !grad_offset)) return DP_ERR_INVALID_ARG;
+  for (int l = 0; l < L; ++l) {
+    if (!dims_ok(dt, B, layers[l].T, layers[l].d_in, layers[l].d_out)) return DP_ERR_INVALID_ARG;
+    if (layers[l].path != DP_PATH_GHOST && layers[l].path != DP_PATH_PEREX) return DP_ERR_INVALID_ARG;
+    if (!grads[l] || !aligned16(grads[l])) return DP_ERR_INVALID_ARG;
+    const uint64_t n = (uint64_t)layers[l].d_in * (uint64_t)layers[l].d_out;
+    if (noisy && grad_offset[l] + n < grad_offset[l]) return DP_ERR_INVALID_ARG;
+  }
+  dp_status st = check_kept(layers, L, dt, kept);
+  if (st != DP_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  NoiseSpec spec;
+  spec.grad_offset = grad_offset;
+  spec.lo = shard_offset;
+  spec.hi = shard_offset + shard_count;
+  spec.stddev = noisy ? sigma * R : 0.f;
+  spec.seed = seed;
+  spec.step = step;
+  // (1) layers without kept gradients: the contraction over a and g
+  std::vector<dp_layer> sub;
+  std::vector<float*> sub_grads;
+  std::vector<uint64_t> sub_off;
+  for (int l = 0; l < L; ++l)
+    if (!kept || !kept[l]) {
+      sub.push_back(layers[l]);
+      sub_grads.push_back(grads[l]);
+      sub_off.push_back(noisy ? grad_offset[l] : 0);
+    }
+  if (!sub.empty()) {
+    NoiseSpec sub_spec = spec;
+    sub_spec.grad_offset = sub_off.data();
+    st = clipped_grad_impl(sub.data(), (int)sub.size(), dt, B, C, nullptr, sub_grads.data(), accumulate, stream,
+                           noisy ? &sub_spec : nullptr);
+    if (st != DP_OK) return st;
+  }
+  // (2) layers with kept gradients: weighted sums, up to kMaxGroup layers per launch
+  NoiseArgs na = {};
+  na.stddev = spec.stddev;
+  na.step_lo = (uint32_t)step;
+  na.step_hi = (uint32_t)(step >> 32);
+  na.lo = spec.lo;
+  na.hi = spec.hi;
+  na.rk = make_round_keys(seed);
+  int l = 0;
+  while (l < L) {
+    GroupArgs ga;
+    ga.B = B;
+    ga.accumulate = accumulate;
+    ga.f16 = 0;
+    ga.n_layers = 0;
+    int64_t blocks = 0;
+    int members[kMaxGroup];
+    for (; l < L && ga.n_layers < kMaxGroup; ++l) {
+      if (!kept || !kept[l]) continue;
+      const int nb = kept_blocks(layers[l].d_in, layers[l].d_out);
+      if (ga.n_layers > 0 && blocks + nb > INT32_MAX / 2) break;
+      GroupLayer& gl = ga.layer[ga.n_layers];
+      gl.a = kept[l];
+      gl.g = nullptr;
+      gl.out = grads[l];
+      gl.T = layers[l].T;
+      gl.d_in = layers[l].d_in;
+      gl.d_out = layers[l].d_out;
+      gl.path = DP_PATH_PEREX;
+      gl.tile_begin = (int)blocks;
+      gl.sq_index = l;
+      gl.part_begin = 0;
+      gl.tiles_per_sample = nb;
+      gl.c_off = 0;
+      // the kernel adds the noise when the layer starts on a generator block; else a pass afterwards
+      na.layer_off[ga.n_layers] = noisy && (grad_offset[l] & 3) == 0 ? grad_offset[l] : ~(uint64_t)0;
+      members[ga.n_layers] = l;
+      blocks += nb;
+      ++ga.n_layers;
+    }
+    if (ga.n_layers == 0) break;
+    ga.total_blocks = (int)blocks;
+    st = launch_kept_weighted_sum(ga, C, na, s);
+    if (st != DP_OK) return st;
+    for (int j = 0; j < ga.n_layers; ++j)
+      if (noisy && na.layer_off[j] == ~(uint64_t)0) {
+        st = noise_after(&spec, members[j], layers[members[j]], grads[members[j]], s);
+        if (st != DP_OK) return st;
+      }
+  }
+  return DP_OK;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------
 // Layer-wise clipping without book-keeping (section 3.3 (II); appendix on the hook-free form).
 // ---------------------------------------------------------------------------------
 namespace {
@@ -752,7 +883,7 @@ int64_t dp_ghost_tile_order(int T, int B, int32_t* sample, int32_t* token_row0, 
   const int64_t n = (int64_t)tps * B;
   if (n > INT32_MAX / 2) return -1;
   for (int64_t b = 0; b < n && b < capacity; ++b) {
-    const GhostTile t = ghost_tile_of(T, B, tps, ghost_logical_tile((int)b, (int)n));
+    const GhostTile t = ghost_tile_of(T, tps, ghost_logical_tile((int)b, (int)n));
     if (sample) sample[b] = t.sample;
     if (token_row0) token_row0[b] = t.I * 256;
     if (token_col0) token_col0[b] = t.J * 128;

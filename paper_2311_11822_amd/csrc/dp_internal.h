@@ -150,6 +150,12 @@ bool clipped_grad_big_supports(int T, int d, int p);
 dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, const NoiseArgs* noise,
                                         hipStream_t s);
 
+// Clip-weighted sum of kept per-sample gradients (kept.hip).  ga.layer[j]: a = kept [B, d * p] fp32,
+// out = grad, tile_begin = first workgroup (kept_blocks(d, p) per layer), c_off; noise as NoiseArgs,
+// layer_off[j] == ~0 switching it off for layer j.
+int kept_blocks(int d, int p);
+dp_status launch_kept_weighted_sum(const GroupArgs& ga, const float* C, const NoiseArgs& na, hipStream_t s);
+
 // Layer-wise clipping in one pass for layers that fit one workgroup tile (layerwise.hip).
 // Shape class of a d x p layer (0: up to 128 x 128, 1: up to 512 x 32, 2: up to 32 x 512), or -1.
 int layerwise_fused_shape(int d, int p);

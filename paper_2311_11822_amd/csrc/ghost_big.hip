@@ -95,7 +95,7 @@ ghost_big_kernel(const GroupArgs ga, float* __restrict__ partials) {
   const int l = layer_of(ga, logical);
   const GroupLayer& ly = ga.layer[l];
   const int T = ly.T;
-  const GhostTile gt = ghost_tile_of(T, ga.B, ly.tiles_per_sample, logical - ly.tile_begin);
+  const GhostTile gt = ghost_tile_of(T, ly.tiles_per_sample, logical - ly.tile_begin);
   const int sample = gt.sample, I = gt.I, J = gt.J;
   const int q = J - 2 * I;                        // position in the tile row: 0 holds the diagonal
   const int r0 = I * TI, c0 = J * TJ;

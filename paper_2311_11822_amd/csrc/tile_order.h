@@ -45,81 +45,34 @@ __host__ __device__ __forceinline__ int grad_logical_tile(int block, int total) 
 }
 
 // ---------------------------------------------------------------------------------
-// Ghost norm: 256 x 128 tiles (I, J), J >= 2 I, of the T x T Gram matrices of each sample.
-//
-// All tiles of one sample read that sample's token rows, tile (I, J) the 256 rows of block I and
-// the 128 rows of block J, over the whole width d_in + d_out.  A sample's rows at T = 2048 are
-// far larger than an XCD's L2, so rows are shared only by tiles that sweep the width together:
-// the 32 tiles an XCD runs at a time should touch as few distinct rows as possible.  The Gram
-// matrix is cut into super-blocks of 4 tile rows x 8 tile columns (1024 x 1024 tokens).  An
-// off-diagonal super-block holds 32 tiles that read 2048 rows between them; a diagonal one holds
-// the 20 tiles of a triangle, which read 1024.  Enumeration of a layer: first the off-diagonal
-// super-blocks of every sample (each one a run of 32 consecutive numbers, which is what one XCD
-// takes per round), then the diagonal ones.  For T <= 1024 there is one diagonal super-block and
-// the order is sample by sample, tile row by tile row.
+// Ghost norm: 256 x 128 tiles (I, J), J >= 2 I, of the T x T Gram matrices of each sample,
+// numbered sample by sample and, inside a sample, tile row by tile row (row I has nj - 2 I tiles).
+// Consecutive tiles then share their 256-token row block, and every run of 32 tiles that an XCD
+// takes holds a mix of diagonal tiles (a quarter of the loads), tiles whose column block lies
+// inside the row block, and full tiles, so the XCDs' L2 caches see an even load over time.
+// (Measured alternative: numbering by 1024 x 1024-token super-blocks, so that the 32 tiles of an
+// XCD touch as few distinct rows as possible, cut the bytes fetched past L2 by a quarter at
+// T = 2048 and was 6 % slower: runs of 32 full tiles next to runs of cheap ones.)
 // ---------------------------------------------------------------------------------
 struct GhostTile {
   int sample;
   int I, J;     // tile row (256 tokens) and tile column (128 tokens)
-  int slot;     // sample * tiles_per_sample + position: index of the tile's partial sum
+  int slot;     // index of the tile's partial sum among the layer's: sample * tiles_per_sample + position
 };
 
-// Tiles of one sample that lie in off-diagonal super-blocks.
-__host__ __device__ __forceinline__ int ghost_offdiag_tiles(int ni, int nj) {
-  const int ns = (ni + 3) / 4;
-  int n = 0;
-  for (int si = 0; si < ns; ++si) {
-    const int hi = imin(4, ni - 4 * si);
-    for (int sj = si + 1; sj < ns; ++sj) n += hi * imin(8, nj - 8 * sj);
-  }
-  return n;
-}
-
-__host__ __device__ __forceinline__ GhostTile ghost_tile_of(int T, int B, int tiles_per_sample, int e) {
-  const int nj = (T + 127) / 128, ni = (T + 255) / 256, ns = (ni + 3) / 4;
-  const int n_off = ghost_offdiag_tiles(ni, nj), n_diag = tiles_per_sample - n_off;
+__host__ __device__ __forceinline__ GhostTile ghost_tile_of(int T, int tiles_per_sample, int e) {
+  const int nj = (T + 127) / 128;
   GhostTile t;
-  int r;                                                   // position among the sample's tiles
-  if (e < B * n_off) {
-    t.sample = e / n_off;
-    r = e - t.sample * n_off;
-  } else {
-    e -= B * n_off;
-    t.sample = e / n_diag;
-    r = n_off + (e - t.sample * n_diag);
+  t.sample = e / tiles_per_sample;
+  t.slot = e;
+  int q = e - t.sample * tiles_per_sample, I = 0;
+  while (q >= nj - 2 * I) {
+    q -= nj - 2 * I;
+    ++I;
   }
-  t.slot = t.sample * tiles_per_sample + r;
-  t.I = 0;
-  t.J = 0;
-  if (r < n_off) {
-    for (int si = 0; si < ns; ++si) {
-      const int hi = imin(4, ni - 4 * si);
-      for (int sj = si + 1; sj < ns; ++sj) {
-        const int cnt = hi * imin(8, nj - 8 * sj);
-        if (r < cnt) {
-          t.I = 4 * si + r % hi;
-          t.J = 8 * sj + r / hi;
-          return t;
-        }
-        r -= cnt;
-      }
-    }
-    return t;                                              // not reached for e in range
-  }
-  r -= n_off;
-  for (int si = 0; si < ns; ++si) {
-    const int hi = imin(4, ni - 4 * si), w = imin(8, nj - 8 * si);
-    for (int i = 0; i < hi; ++i) {
-      const int cnt = imax(0, w - 2 * i);
-      if (r < cnt) {
-        t.I = 4 * si + i;
-        t.J = 8 * si + 2 * i + r;
-        return t;
-      }
-      r -= cnt;
-    }
-  }
-  return t;                                                // not reached for e in range
+  t.I = I;
+  t.J = 2 * I + q;
+  return t;
 }
 
 // Workgroup id -> tile number of the launch for the ghost-norm kernel.  Each XCD takes runs of

@@ -75,6 +75,26 @@ perex_norm_kernel(const GroupArgs ga, float* __restrict__ partials) {
     __syncthreads();
   }
 
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Book-keeping of the instantiated gradient (appendix A.2 applied to this path): when the
+  // caller provides room, the tile of a_i^T g_i is kept, and the clip-weighted gradient is later
+  // formed as sum_i C_i G_i from these copies instead of a second pass over a and g.
+  if (ly.out) {
+    float* dst = ly.out + (size_t)sample * ly.d_in * ly.d_out;
+    const int wm = (wave / S::WN) * S::WTM, wn = (wave % S::WN) * S::WTN;
+#pragma unroll
+    for (int im = 0; im < S::TM; ++im)
+#pragma unroll
+      for (int jn = 0; jn < S::TN; ++jn) {
+        const int col = t.n0 + wn + jn * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = t.m0 + wm + im * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (row < t.d && col < t.p) dst[(size_t)row * t.p + col] = acc[im][jn][r];
+        }
+      }
+  }
+
   // Rows/columns past the layer's edge were loaded as zeros, so they add nothing.
   float s = 0.f;
 #pragma unroll
@@ -86,7 +106,6 @@ perex_norm_kernel(const GroupArgs ga, float* __restrict__ partials) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
   float* red = reinterpret_cast<float*>(lds);    // all LDS reads finished at the last barrier
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) red[wave] = s;
   __syncthreads();
   if (threadIdx.x == 0) {

@@ -15,7 +15,8 @@ class BkPipeline:
     given as torch.bfloat16 or as int16/uint16 bit patterns, fp16 as torch.float16, fp32 as
     torch.float32."""
 
-    def __init__(self, layers: Sequence[Tuple[torch.Tensor, torch.Tensor]], paths: Optional[List[int]] = None):
+    def __init__(self, layers: Sequence[Tuple[torch.Tensor, torch.Tensor]], paths: Optional[List[int]] = None,
+                 keep_instantiated: bool = True):
         a0 = layers[0][0]
         self.device = a0.device
         self.dt = {torch.float32: dp.DP_F32, torch.float16: dp.DP_F16}.get(a0.dtype, dp.DP_BF16)
@@ -46,19 +47,38 @@ class BkPipeline:
         if ws_bytes == 0:
             raise dp.DpError(dp.DP_ERR_INVALID_ARG, "dp_norms_multi_workspace_bytes")
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device)
+        # Layers on the instantiated path keep their per-sample gradients [B, d, p] between the norm
+        # pass and the gradient pass (smaller than the layer's Gram matrices by the path rule).
+        self.kept = [None] * L
+        if keep_instantiated and self.dt != dp.DP_F32:
+            self.kept = [torch.empty((self.B, d, p), dtype=torch.float32, device=self.device)
+                         if path == dp.DP_PATH_PEREX else None for (_, d, p), path in zip(self.dims, self.paths)]
+        self.any_kept = any(k is not None for k in self.kept)
+        self.kept_ptrs = (dp.C.c_void_p * L)(*[None if k is None else k.data_ptr() for k in self.kept])
 
     def norms(self, stream=None):
-        dp.dp_norms_multi(self.desc, self.dt, self.B, self.sqnorm, self.ws, stream)
+        if self.any_kept:
+            dp.dp_norms_multi_keep(self.desc, self.dt, self.B, self.sqnorm, self.kept_ptrs, self.ws, stream)
+        else:
+            dp.dp_norms_multi(self.desc, self.dt, self.B, self.sqnorm, self.ws, stream)
 
     def clip(self, mode, R, stability=0.01, stream=None):
         dp.dp_clip_factors(self.sqnorm, self.L, self.B, mode, R, stability, self.C, self.norm, stream)
 
     def grad(self, accumulate=0, stream=None):
-        dp.dp_clipped_grad_multi(self.desc, self.dt, self.B, self.C, self.grad_ptrs, accumulate, stream)
+        if self.any_kept:
+            dp.dp_clipped_grad_kept_multi(self.desc, self.dt, self.B, self.C, self.kept_ptrs, self.grad_ptrs, None,
+                                          accumulate, 0, 0, 0.0, 1.0, 0, 0, stream)
+        else:
+            dp.dp_clipped_grad_multi(self.desc, self.dt, self.B, self.C, self.grad_ptrs, accumulate, stream)
 
     def grad_noise(self, sigma, R, seed, step, offset, count, accumulate=0, stream=None):
         """Gradients with the noise added in the same pass (elements [offset, offset + count) of
         the flattened gradient)."""
+        if self.any_kept:
+            dp.dp_clipped_grad_kept_multi(self.desc, self.dt, self.B, self.C, self.kept_ptrs, self.grad_ptrs,
+                                          self.grad_offsets, accumulate, offset, count, sigma, R, seed, step, stream)
+            return
         dp.dp_clipped_grad_noise_multi(self.desc, self.dt, self.B, self.C, self.grad_ptrs, self.grad_offsets,
                                        accumulate, offset, count, sigma, R, seed, step, stream)
 

@@ -156,13 +156,3 @@ def test_ghost_tile_order_is_a_bijection(dp, T, B):
     # partial-sum slots: each used once, and a sample's slots are contiguous
     assert sorted(slot.tolist()) == list(range(B * tps))
     assert np.all(slot // tps == sample)
-
-
-def test_ghost_tile_order_groups_rows_for_long_sequences(dp):
-    # T = 2048: a run of 32 consecutive workgroups of one XCD in the first part of a layer is one
-    # off-diagonal super-block of one sample: 4 tile rows x 8 tile columns, 2048 distinct token rows
-    sample, r0, c0, _ = dp.dp_ghost_tile_order(2048, 4)
-    ids = 0 + 8 * np.arange(32)                       # XCD 0, first round
-    assert len(np.unique(sample[ids])) == 1
-    assert len(np.unique(r0[ids])) == 4 and len(np.unique(c0[ids])) == 8
-    assert np.all(c0[ids] >= 1024) and np.all(r0[ids] < 1024)

@@ -326,15 +326,18 @@ def test_bf16_unclipped_is_plain_product(dp):
     assert frob(host(grad), want) <= 1e-5
 
 
+@pytest.mark.parametrize("keep", [False, True])
 @pytest.mark.parametrize("dtype", HALF_TYPES)
-def test_multi_layer_stack_mixed_paths(dp, Pipe, dtype):
-    # A stack whose layers take different norm paths and shapes, in one grouped launch each.
+def test_multi_layer_stack_mixed_paths(dp, Pipe, dtype, keep):
+    # A stack whose layers take different norm paths and shapes, in one grouped launch each;
+    # with `keep`, the instantiated layers' gradients come from the kept per-sample gradients.
     dims = [(72, 264), (264, 72), (8, 8), (136, 136), (520, 16)]
     w = si.small_workload("m", dtype, 3, 150, dims, clip_mode=si.CLIP_AUTOMATIC)
     layers = gen(w)
     l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
     paths = [0, 1, 1, 0, 1]
-    pipe = Pipe([(dev(a), dev(g)) for a, g in layers], paths=paths)
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers], paths=paths, keep_instantiated=keep)
+    assert pipe.any_kept == keep
     pipe.norms()
     pipe.clip(w.clip_mode, w.R, w.stability)
     pipe.grad()
@@ -766,6 +769,109 @@ def test_pipeline_layerwise_step(dp, Pipe):
     z = (host(pipe.flat).astype(np.float64) - clean) / o.group_noise_std(sigma, R)
     want = o.normals(seed, step, 0, pipe.psi)
     assert np.all(np.abs(z - want) <= 2e-5 * np.maximum(1.0, np.abs(want)))
+
+
+# ----------------------------------------------------------------------------
+# instantiated layers with their per-sample gradients kept (dp_norms_multi_keep,
+# dp_clipped_grad_kept_multi)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", HALF_TYPES)
+def test_kept_per_sample_gradients(dp, dtype):
+    # three layers on the instantiated path (several tiles with ragged edges; one tile; tiny) and
+    # one on the ghost path; offsets chosen so that one kept layer starts off a generator block
+    B, T = 4, 264
+    dims = [(264, 392), (136, 72), (8, 16), (392, 520)]
+    gaps = [0, 2, 0, 6]
+    w = si.small_workload("kp", dtype, B, T, dims)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    DT = dt_of(dp, dtype)
+    paths = [dp.dp_choose_path(T, d, p) for d, p in dims]
+    assert paths == [1, 1, 1, 0]
+    desc = dp.layer_array([(dev(a), dev(g), T, d, p, path) for (a, g), (d, p), path in zip(layers, dims, paths)])
+    keep_alive = [(dev(a), dev(g)) for a, g in layers]
+    desc = dp.layer_array([(a, g, T, d, p, path) for (a, g), (d, p), path in zip(keep_alive, dims, paths)])
+    L = len(dims)
+    kept = [torch.full((B, d, p), 7.0, dtype=torch.float32, device="cuda") if path == 1 else None
+            for (d, p), path in zip(dims, paths)]
+    ws = torch.empty(dp.dp_norms_multi_workspace_bytes(desc, DT, B), dtype=torch.uint8, device="cuda")
+    sqn = torch.zeros((L, B), dtype=torch.float32, device="cuda")
+    dp.dp_norms_multi_keep(desc, DT, B, sqn, kept, ws)
+    plain = torch.zeros((L, B), dtype=torch.float32, device="cuda")
+    dp.dp_norms_multi(desc, DT, B, plain, ws)
+    assert torch.equal(sqn, plain)                                   # keeping does not change the norms
+    want_sqn = np.stack([o.perex_sqnorm(a, g) for a, g in l64])
+    assert rel(host(sqn), want_sqn) <= TOL_BF16_NORM
+    for l, (a, g) in enumerate(l64):
+        if kept[l] is None:
+            continue
+        got = host(kept[l])
+        for i in range(B):
+            assert frob(got[i], a[i].T @ g[i]) <= 1e-5, (l, i)      # the instantiated per-sample gradient
+    C = np.array([0.3, 0.0, 1.0, 1e-3], dtype=np.float32)
+    Cd = dev(C)
+    offs, acc = [], 10 ** 9
+    for (d, p), gap in zip(dims, gaps):
+        acc += gap
+        offs.append(acc)
+        acc += d * p
+    total_lo, total_hi = offs[0], acc
+    sigma, R, seed, step = 0.7, 1.3, 99, 6
+    grads = lambda fill: [torch.full((d, p), fill, dtype=torch.float32, device="cuda") for d, p in dims]
+    for accumulate in (0, 1):
+        for lo, cnt in ((total_lo, total_hi - total_lo), (offs[0] + 1001, 50000), (offs[1] + 3, 8), (0, 0)):
+            ref = grads(0.5)
+            dp.dp_clipped_grad_multi(desc, DT, B, Cd, ref, accumulate)
+            for l, (d, p) in enumerate(dims):
+                x0, x1 = max(offs[l], lo), min(offs[l] + d * p, lo + cnt)
+                if x0 < x1:
+                    dp.dp_add_noise(ref[l].view(-1).data_ptr() + 4 * (x0 - offs[l]), x0, x1 - x0, sigma, R, seed, step)
+            got = grads(0.5)
+            dp.dp_clipped_grad_kept_multi(desc, DT, B, Cd, kept, got, offs, accumulate, lo, cnt, sigma, R, seed, step)
+            for l in range(L):
+                if kept[l] is None:
+                    assert torch.equal(got[l], ref[l])               # same kernels as without kept layers
+                else:                                                # other summation order, same noise values
+                    G = o.clipped_grad(l64[l][0], l64[l][1], C.astype(np.float64))
+                    scale = np.sqrt(np.mean(G * G))
+                    assert np.max(np.abs(host(got[l]) - host(ref[l]))) <= 2e-5 * scale + 1e-6 * (sigma * R if cnt else 0) * 6
+    # against the oracle, no noise
+    got = grads(-1.0)
+    dp.dp_clipped_grad_kept_multi(desc, DT, B, Cd, kept, got, None, 0, 0, 0, 0.0, 1.0, 0, 0)
+    for l, (a, g) in enumerate(l64):
+        assert frob(host(got[l]), o.clipped_grad(a, g, C.astype(np.float64))) <= 1e-5
+    # refusals: a kept buffer for a ghost-path layer; fp32 storage
+    bad = list(kept)
+    bad[3] = torch.zeros((B, 392, 520), dtype=torch.float32, device="cuda")
+    with pytest.raises(dp.DpError) as err:
+        dp.dp_norms_multi_keep(desc, DT, B, sqn, bad, ws)
+    assert err.value.status == dp.DP_ERR_INVALID_ARG
+
+
+def test_kept_gradients_whole_pipeline_cfg3_noise_is_bit_identical(dp, Pipe):
+    # cfg3 with kept gradients: gradient + noise in one call equals gradient, then dp_add_noise
+    w = si.WORKLOADS["cfg3"]
+    layers = gen(w)
+    pipe = Pipe([(dev(a), dev(g)) for a, g in layers])
+    assert pipe.any_kept and all(k is not None for k in pipe.kept)
+    pipe.norms()
+    pipe.clip(w.clip_mode, w.R, w.stability)
+    off, cnt = 1000, w.psi - 3000
+    pipe.grad()
+    pipe.noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+    two = pipe.flat.clone()
+    pipe.flat.fill_(4.0)
+    pipe.grad_noise(w.sigma, w.R, w.noise_seed, w.noise_step, off, cnt)
+    assert torch.equal(pipe.flat, two)
+    # and the GEMM path on the same layers agrees to rounding
+    gemm = Pipe([(dev(a), dev(g)) for a, g in layers], keep_instantiated=False)
+    gemm.norms()
+    gemm.clip(w.clip_mode, w.R, w.stability)
+    gemm.grad()
+    pipe.grad()
+    assert torch.equal(gemm.C, pipe.C)
+    assert frob(host(pipe.flat), host(gemm.flat)) <= 1e-5
 
 
 # ----------------------------------------------------------------------------
