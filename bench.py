@@ -64,6 +64,17 @@ def ghost_flops_executed(w):
     return total
 
 
+def grad_flops_executed(w):
+    """Flops the gradient stage issues: the contraction 2 B T d p per layer, except for layers on
+    the instantiated path, whose gradient is the weighted sum of the per-sample gradients kept by
+    the norm kernel (2 B d p)."""
+    total = 0.0
+    for d, p in w.layers:
+        kept = w.dtype != si.F32 and 2 * w.T * w.T > d * p
+        total += 2.0 * w.B * d * p if kept else 2.0 * w.B * w.T * d * p
+    return total
+
+
 def cpu_baseline(w, layer_ids, n_samples):
     """The oracle as it stands on the host cores, on a bounded sample of the workload: the whole
     path (norms, clip factors, gradient, noise on the same fraction of the elements) on the listed
@@ -180,6 +191,8 @@ def measure(name, args, torch, BkPipeline, noise_pass=False):
     per_step = stage.sum(axis=1)               # event time of each step, first norm kernel to last kernel
     norm_flops, grad_flops = workload_flops(w)
     norm_exec = ghost_flops_executed(w)
+    grad_exec = grad_flops_executed(w)
+    kept_bytes = sum(4.0 * (w.B + 1) * d * p for d, p in w.layers if w.dtype != si.F32 and 2 * w.T * w.T > d * p)
     grad_launches = -(-w.L // 48) if w.dtype != si.F32 else w.L
     res = {
         "workload": f"{w.name}: B={w.B} T={w.T} L={w.L} layers, psi={w.psi}",
@@ -193,16 +206,21 @@ def measure(name, args, torch, BkPipeline, noise_pass=False):
         "stage_ms": {"norms": float(ms_norm), "clip": float(ms_clip), "grad": float(ms_grad), "noise": float(ms_noise)},
         # executed = what the kernels issue (the ghost-norm kernel skips the lower triangle of the
         # symmetric Gram matrices); model = the paper's operation counts (complexity table, section 3)
-        "tflops_executed": (norm_exec + grad_flops) / (ms_step * 1e-3) / 1e12,
-        "pct_bf16_peak": 100.0 * (norm_exec + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
+        "tflops_executed": (norm_exec + grad_exec) / (ms_step * 1e-3) / 1e12,
+        "pct_bf16_peak": 100.0 * (norm_exec + grad_exec) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "tflops_model": (norm_flops + grad_flops) / (ms_step * 1e-3) / 1e12,
         "pct_bf16_peak_model_flops": 100.0 * (norm_flops + grad_flops) / (ms_step * 1e-3) / PEAK_BF16_FLOPS,
         "norm_stage": {"tflops_model": norm_flops / (ms_norm * 1e-3) / 1e12,
                        "tflops_executed": norm_exec / (ms_norm * 1e-3) / 1e12},
-        "grad_stage": {"tflops": grad_flops / (ms_grad * 1e-3) / 1e12,
-                       "frac_bf16_peak": grad_flops / (ms_grad * 1e-3) / PEAK_BF16_FLOPS,
+        # layers on the instantiated path take their gradient from the kept per-sample gradients
+        # (kept_weighted_sum_kernel: B + 1 arrays of d p floats move), the others from the
+        # contraction over a and g (clipped_grad_big_kernel)
+        "grad_stage": {"tflops": grad_exec / (ms_grad * 1e-3) / 1e12,
+                       "frac_bf16_peak": grad_exec / (ms_grad * 1e-3) / PEAK_BF16_FLOPS,
                        "launches_per_step": grad_launches,
-                       "flops_per_step": grad_flops},
+                       "flops_per_step": grad_exec,
+                       "kept_gradient_bytes": kept_bytes,
+                       "kept_gradient_gbps": kept_bytes / (ms_grad * 1e-3) / 1e9 if kept_bytes else None},
     }
     if noise_pass:
         # the separate noise pass on this workload's shard: 4 bytes read + 4 written per element
@@ -279,11 +297,12 @@ def main():
             per_config[name] = r
 
     # Bytes per launch that missed the XCDs' L2 caches (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled
-    # by what the same counters read for a device copy of known size): profiles/hbm_traffic.json,
-    # written from the committed counter runs; null when this workload has not been profiled.
+    # by what the same counters read for a device copy of known size; served by the memory-side
+    # cache or by HBM): profiles/l2_miss_traffic.json, written from the committed counter runs;
+    # null when this workload has not been profiled.
     traffic = None
     try:
-        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+        with open(os.path.join(ROOT, "profiles", "l2_miss_traffic.json")) as f:
             per = json.load(f)["per_launch"][w.name]
         traffic = sum(per[k]["fetch_bytes"] + per[k]["write_bytes"]
                       for k in ("clipped_grad_big_kernel", "clipped_grad_tail_kernel") if k in per)

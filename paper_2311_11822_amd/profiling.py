@@ -10,8 +10,9 @@
       the average duration from the dispatch timestamps and the average of every counter
       found in rocprofv3's csv output below each DIR; where the counters are there, also the L2
       hit rate (TCC_HIT / (TCC_HIT + TCC_MISS)) and the shader clock the kernel ran at
-      (4 x SQ_WAVE_CYCLES / (1024 waves x duration), meaningful for kernels that keep one
-      256-thread workgroup on each of the 256 compute units for their whole duration).
+      (4 x SQ_WAVE_CYCLES / (1024 waves x duration), printed for the large-tile kernels, which
+      keep one 256-thread workgroup on each of the 256 compute units; a lower bound when the last
+      round of workgroups does not fill the chip).
 
   python -m paper_2311_11822_amd.profiling gemm-yardstick
       times the library GEMM (torch.matmul -> hipBLASLt) on the transposed-A products of the
@@ -73,7 +74,7 @@ def summarize(dirs) -> None:
                     extra = ""
                     if "TCC_HIT_sum" in vals[k] and vals[k]["TCC_HIT_sum"] + vals[k]["TCC_MISS_sum"] > 0:
                         extra += f"; L2 hit rate = {vals[k]['TCC_HIT_sum'] / (vals[k]['TCC_HIT_sum'] + vals[k]['TCC_MISS_sum']):.3f}"
-                    if "SQ_WAVE_CYCLES" in vals[k] and "SQ_WAVES" in vals[k] and vals[k]["SQ_WAVES"] / n >= 1024:
+                    if "SQ_WAVE_CYCLES" in vals[k] and "big_kernel" in k and vals[k].get("SQ_WAVES", 0) / n >= 1024:
                         extra += f"; shader clock = {4.0 * vals[k]['SQ_WAVE_CYCLES'] / (1024 * dur[k]):.2f} GHz"
                     print(f"{k}: launches = {n}, avg duration = {dur[k] / n / 1e3:.1f} us, per launch: {line}{extra}")
             elif base.endswith("kernel_stats.csv"):
