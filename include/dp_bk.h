@@ -239,6 +239,22 @@ dp_status dp_clipped_grad_noise_multi(const dp_layer* layers, int L, dp_dtype dt
                                       uint64_t seed, uint64_t step, void* stream);
 
 /*
+ * dp_clipped_grad_noise_multi with the gradient stored in 16 bits, in the storage type of a and g
+ * (mixed-precision training keeps parameters, activations and gradients in half precision:
+ * section 2.3): the fp32 value that dp_clipped_grad_noise_multi would store -- weighted sum, plus
+ * the old value widened to fp32 when accumulate == 1, plus the noise -- is rounded once, to nearest
+ * even, to bf16 (dt == DP_BF16) or IEEE binary16 (dt == DP_F16).
+ *   grads16   HOST array of L device pointers, grads16[l] -> [d_in_l, d_out_l] of type dt, 16-byte aligned
+ * Only the large-tile kernels write 16-bit gradients: every layer needs d_in, d_out >= 128, T a
+ * multiple of 32, a sample's a and g below 2 GiB each, and (when sigma > 0) a grad_offset that is a
+ * multiple of 4; otherwise, and for dt == DP_F32, DP_ERR_UNSUPPORTED (nothing is enqueued).
+ */
+dp_status dp_clipped_grad_noise_multi_h16(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                          void* const* grads16, const uint64_t* grad_offset, int accumulate,
+                                          uint64_t shard_offset, uint64_t shard_count, float sigma, float R,
+                                          uint64_t seed, uint64_t step, void* stream);
+
+/*
  * Group-wise clipping (eq. (1) with M groups; section 2.1, "Mathematical gradient partition":
  * all-layer clipping is one group, layer-wise clipping one group per layer, the paper's default).
  * The rows of sqnorm (one per layer weight, plus one per bias when biases are trained) are

@@ -46,6 +46,8 @@ _PROTOS = {
     "dp_clipped_grad_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp), _i, _vp]),
     "dp_clipped_grad_noise_multi": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp),
                                         C.POINTER(_u64), _i, _u64, _u64, _f, _f, _u64, _u64, _vp]),
+    "dp_clipped_grad_noise_multi_h16": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(_vp),
+                                            C.POINTER(_u64), _i, _u64, _u64, _f, _f, _u64, _u64, _vp]),
     "dp_clip_factors_grouped": (_i, [_vp, _i, _i, C.POINTER(C.c_int32), _i, C.POINTER(_f), _i, _f, _vp, _vp, _vp]),
     "dp_clipped_grad_grouped": (_i, [C.POINTER(dp_layer), _i, _i, _i, _vp, C.POINTER(C.c_int32), _i,
                                      C.POINTER(_vp), _i, _vp]),
@@ -179,6 +181,18 @@ def dp_clipped_grad_noise_multi(layers, dt, B, Cf, grads, grad_offset, accumulat
     _check(lib.dp_clipped_grad_noise_multi(arr, len(arr), dt, B, _ptr(Cf), gp, offs, accumulate, shard_offset,
                                            shard_count, sigma, R, seed, step, _stream(stream)),
            "dp_clipped_grad_noise_multi")
+
+
+def dp_clipped_grad_noise_multi_h16(layers, dt, B, Cf, grads16, grad_offset, accumulate, shard_offset, shard_count,
+                                    sigma, R, seed, step, stream=None) -> None:
+    arr = layers if isinstance(layers, C.Array) else layer_array(layers)
+    gp = grads16 if isinstance(grads16, C.Array) else (C.c_void_p * len(grads16))(*[_ptr(x) for x in grads16])
+    offs = None
+    if grad_offset is not None:
+        offs = grad_offset if isinstance(grad_offset, C.Array) else (C.c_uint64 * len(grad_offset))(*grad_offset)
+    _check(lib.dp_clipped_grad_noise_multi_h16(arr, len(arr), dt, B, _ptr(Cf), gp, offs, accumulate, shard_offset,
+                                               shard_count, sigma, R, seed, step, _stream(stream)),
+           "dp_clipped_grad_noise_multi_h16")
 
 
 def _i32(xs):

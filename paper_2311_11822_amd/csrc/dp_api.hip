@@ -265,9 +265,11 @@ dp_status noise_after(const NoiseSpec* noise, int l, const dp_layer& ly, float* 
   return launch_noise(grad + (lo - begin), lo, hi - lo, noise->stddev, noise->seed, noise->step, s);
 }
 
+// out16: grads[l] address 16-bit arrays of the operands' storage type; only the large-tile kernels
+// write those, with the noise in their epilogue, so every layer must qualify for them.
 dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
                             const int* c_off, float* const* grads, int accumulate, void* stream,
-                            const NoiseSpec* noise = nullptr) {
+                            const NoiseSpec* noise = nullptr, bool out16 = false) {
   if (!dtype_ok(dt)) return DP_ERR_INVALID_ARG;
   if (!layers || !grads || !C || L <= 0 || B <= 0) return DP_ERR_INVALID_ARG;
   if (accumulate != 0 && accumulate != 1) return DP_ERR_INVALID_ARG;
@@ -279,6 +281,15 @@ dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, c
     if ((int64_t)clipped_grad_tiles(layers[l].d_in, layers[l].d_out) > INT32_MAX / 2) return DP_ERR_INVALID_ARG;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (out16) {
+    if (dt == DP_F32) return DP_ERR_UNSUPPORTED;
+    for (int l = 0; l < L; ++l) {
+      const dp_layer& ly = layers[l];
+      if (!(ly.d_in >= 128 && ly.d_out >= 128 && clipped_grad_big_supports(ly.T, ly.d_in, ly.d_out)))
+        return DP_ERR_UNSUPPORTED;
+      if (noise && (noise->grad_offset[l] & 3)) return DP_ERR_UNSUPPORTED;
+    }
+  }
   if (dt == DP_F32) {
     for (int l = 0; l < L; ++l) {
       dp_status st = launch_clipped_grad_f32(static_cast<const float*>(layers[l].a),
@@ -350,7 +361,7 @@ dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, c
         na.hi = noise->hi;
         na.rk = make_round_keys(noise->seed);
       }
-      dp_status st = pass == 0 ? launch_clipped_grad_big_group(ga, C, fused ? &na : nullptr, s)
+      dp_status st = pass == 0 ? launch_clipped_grad_big_group(ga, C, fused ? &na : nullptr, s, out16)
                                : launch_clipped_grad_group(ga, C, s);
       if (st != DP_OK) return st;
       if (noise && !fused) {
@@ -396,6 +407,31 @@ dp_status dp_clipped_grad_noise_multi(const dp_layer* layers, int L, dp_dtype dt
   spec.seed = seed;
   spec.step = step;
   return clipped_grad_impl(layers, L, dt, B, C, nullptr, grads, accumulate, stream, &spec);
+}
+
+dp_status dp_clipped_grad_noise_multi_h16(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
+                                          void* const* grads16, const uint64_t* grad_offset, int accumulate,
+                                          uint64_t shard_offset, uint64_t shard_count, float sigma, float R,
+                                          uint64_t seed, uint64_t step, void* stream) {
+  if (!(sigma >= 0.f) || isinf(sigma)) return DP_ERR_INVALID_ARG;
+  if (!(R > 0.f)) return DP_ERR_INVALID_ARG;
+  if (shard_offset + shard_count < shard_offset) return DP_ERR_INVALID_ARG;
+  float* const* grads = reinterpret_cast<float* const*>(grads16);      // the kernels store 16-bit values there
+  if (sigma == 0.f || shard_count == 0)
+    return clipped_grad_impl(layers, L, dt, B, C, nullptr, grads, accumulate, stream, nullptr, true);
+  if (isinf(R) || !grad_offset || !layers || L <= 0) return DP_ERR_INVALID_ARG;
+  for (int l = 0; l < L; ++l) {
+    const uint64_t n = (uint64_t)std::max(layers[l].d_in, 0) * (uint64_t)std::max(layers[l].d_out, 0);
+    if (grad_offset[l] + n < grad_offset[l]) return DP_ERR_INVALID_ARG;
+  }
+  NoiseSpec spec;
+  spec.grad_offset = grad_offset;
+  spec.lo = shard_offset;
+  spec.hi = shard_offset + shard_count;
+  spec.stddev = sigma * R;
+  spec.seed = seed;
+  spec.step = step;
+  return clipped_grad_impl(layers, L, dt, B, C, nullptr, grads, accumulate, stream, &spec, true);
 }
 
 dp_status dp_clipped_grad_grouped(const dp_layer* layers, int L, dp_dtype dt, int B, const float* C,
@@ -490,7 +526,7 @@ dp_status check_kept(const dp_layer* layers, int L, dp_dtype dt, float* const* k
     if (!kept[l]) continue;
     if (dt == DP_F32) return DP_ERR_UNSUPPORTED;
     if (layers[l].path != DP_PATH_PEREX || !aligned16(kept[l])) return DP_ERR_INVALID_ARG;
-    if ((int64_t)layers[l].d_in * layers[l].d_out > INT32_MAX) return DP_ERR_INVALID_ARG;
+    if ((int64_t)layers[l].d_in * layers[l].d_out > INT32_MAX - 4096) return DP_ERR_INVALID_ARG;   // int element index
   }
   return DP_OK;
 }

@@ -146,9 +146,10 @@ int clipped_grad_big_tiles(int d, int p);
 // Of a launch of n large tiles, how many (the last ones) go to the sub-tile kernel.
 int clipped_grad_big_tail_tiles(int n);
 bool clipped_grad_big_supports(int T, int d, int p);
-// noise == nullptr: gradients only.
+// noise == nullptr: gradients only.  out16: the layers' `out` pointers address 16-bit arrays of the
+// operands' storage type (bf16 or fp16) instead of fp32.
 dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, const NoiseArgs* noise,
-                                        hipStream_t s);
+                                        hipStream_t s, bool out16 = false);
 
 // Clip-weighted sum of kept per-sample gradients (kept.hip).  ga.layer[j]: a = kept [B, d * p] fp32,
 // out = grad, tile_begin = first workgroup (kept_blocks(d, p) per layer), c_off; noise as NoiseArgs,

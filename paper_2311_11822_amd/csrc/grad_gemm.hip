@@ -96,6 +96,56 @@ __device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& lay
   n0 = tn * BN;
 }
 
+// 16-bit gradient output (mixed-precision training keeps gradients in the storage type of the
+// activations: section 2.3 of the paper): the fp32 value - weighted sum, old value when
+// accumulating, noise - is rounded once, to nearest even, to bf16 or IEEE binary16.
+template <bool F16>
+__device__ __forceinline__ uint16_t to_half_bits(float x) {
+  if constexpr (F16) {
+    return __builtin_bit_cast(uint16_t, (_Float16)x);
+  } else {
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;                    // NaN stays NaN
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+  }
+}
+template <bool F16>
+__device__ __forceinline__ float from_half_bits(uint16_t h) {
+  if constexpr (F16)
+    return (float)__builtin_bit_cast(_Float16, h);
+  else
+    return __uint_as_float((uint32_t)h << 16);
+}
+
+// Four consecutive outputs of one row: (+)= and store, fp32 (16 bytes) or 16-bit (8 bytes).
+template <bool F16, bool OUT16, bool ACCUMULATE>
+__device__ __forceinline__ void load_old4(const float* out32, size_t index, float (&old)[4]) {
+  if constexpr (!ACCUMULATE) {
+    old[0] = old[1] = old[2] = old[3] = 0.f;
+  } else if constexpr (OUT16) {
+    const uint2 w = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(out32) + index);
+    old[0] = from_half_bits<F16>((uint16_t)(w.x & 0xFFFFu));
+    old[1] = from_half_bits<F16>((uint16_t)(w.x >> 16));
+    old[2] = from_half_bits<F16>((uint16_t)(w.y & 0xFFFFu));
+    old[3] = from_half_bits<F16>((uint16_t)(w.y >> 16));
+  } else {
+    const f32x4v w = *reinterpret_cast<const f32x4v*>(out32 + index);
+    old[0] = w[0]; old[1] = w[1]; old[2] = w[2]; old[3] = w[3];
+  }
+}
+template <bool F16, bool OUT16>
+__device__ __forceinline__ void store4(float* out32, size_t index, const float* v) {
+  if constexpr (OUT16) {
+    uint2 w;
+    w.x = (uint32_t)to_half_bits<F16>(v[0]) | ((uint32_t)to_half_bits<F16>(v[1]) << 16);
+    w.y = (uint32_t)to_half_bits<F16>(v[2]) | ((uint32_t)to_half_bits<F16>(v[3]) << 16);
+    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out32) + index) = w;
+  } else {
+    const f32x4v w = {v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4v*>(out32 + index) = w;
+  }
+}
+
 // The kernel's copy of what tile_noise needs, read once from the kernel arguments into registers.
 struct TileNoise {
   float stddev;
@@ -153,7 +203,7 @@ __device__ __forceinline__ void tile_noise(float (&v)[16], const TileNoise& na, 
   }
 }
 
-template <bool F16, bool NOISE>
+template <bool F16, bool NOISE, bool OUT16>
 __global__ void __launch_bounds__(NT)
 clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, const NoiseArgs na) {
   // The weights do not change during the kernel: read them through the constant address space
@@ -388,12 +438,12 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, 
       for (int y = 0; y < 4; ++y) {
         const int row = m0 + wm + x * 32 + (lane & 31);
         const int col0 = n0 + wn + y * 32 + 4 * (lane >> 5);
-        f32x4v* base = reinterpret_cast<f32x4v*>(out + (size_t)row * p + col0);   // + 2 q: columns col0 + 8 q ..
+        const size_t base = (size_t)row * p + col0;                  // + 8 q: columns col0 + 8 q ..
         float v[16];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          f32x4v old = {0.f, 0.f, 0.f, 0.f};
-          if (accumulate && row < d && col0 + 8 * q < p) old = base[2 * q];
+          float old[4] = {0.f, 0.f, 0.f, 0.f};
+          if (accumulate && row < d && col0 + 8 * q < p) load_old4<F16, OUT16, accumulate>(out, base + 8 * q, old);
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
             const float t = acc[x][y][4 * q + k] * held;
@@ -403,10 +453,7 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, 
         if (NOISE) tile_noise(v, tn, m0 + wm + x * 32, n0 + wn + y * 32, d, p, lane);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          if (row < d && col0 + 8 * q < p) {
-            const f32x4v w = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
-            base[2 * q] = w;
-          }
+          if (row < d && col0 + 8 * q < p) store4<F16, OUT16>(out, base + 8 * q, v + 4 * q);
         __builtin_amdgcn_sched_barrier(0);
       }
   };
@@ -443,7 +490,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 // conditional: the number of loads in flight is a compile-time constant and a thread waits only
 // for the slot it is about to store.  Two LDS stages, one barrier per k-block.  The k-steps of an output element are added in
 // the same order as in the large kernel.
-template <class S, int D, bool F16, bool NOISE>
+template <class S, int D, bool F16, bool NOISE, bool OUT16>
 __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int B, int accumulate,
                                                        const NoiseArgs& na, int layer, int m0, int n0,
                                                        const __attribute__((address_space(4))) float* C,
@@ -570,12 +617,12 @@ __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int
   // epilogue in the transposed layout described at tile_noise
   float* out = ly.out;
   const int row = m0 + wm + (lane & 31), col0 = n0 + wn + 4 * (lane >> 5);
-  f32x4v* base = reinterpret_cast<f32x4v*>(out + (size_t)row * p + col0);
+  const size_t base = (size_t)row * p + col0;
   float v[16];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    f32x4v old = {0.f, 0.f, 0.f, 0.f};
-    if (accumulate && row < d && col0 + 8 * q < p) old = base[2 * q];
+    float old[4] = {0.f, 0.f, 0.f, 0.f};
+    if (accumulate && row < d && col0 + 8 * q < p) load_old4<F16, OUT16, true>(out, base + 8 * q, old);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const float t = acc[0][0][4 * q + k] * held;
@@ -585,10 +632,7 @@ __device__ __forceinline__ void clipped_grad_tile_deep(const GroupLayer& ly, int
   if (NOISE) tile_noise(v, load_tile_noise(na, layer), m0 + wm, n0 + wn, d, p, lane);
 #pragma unroll
   for (int q = 0; q < 4; ++q)
-    if (row < d && col0 + 8 * q < p) {
-      const f32x4v w = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
-      base[2 * q] = w;
-    }
+    if (row < d && col0 + 8 * q < p) store4<F16, OUT16>(out, base + 8 * q, v + 4 * q);
 }
 
 // Sub-tiles are 64 x 64 (16 per tile), k-blocks of 64 rows, four k-blocks in flight: three
@@ -597,7 +641,7 @@ using TailShape = TnShape<DP_TAIL_SHAPE>;
 constexpr int TAIL = 64, SUBS_N = BN / TAIL, SUBS = (BM / TAIL) * SUBS_N;
 static_assert(TailShape::BM == TAIL && TailShape::BN == TAIL, "sub-tile shape");
 
-template <bool F16, bool NOISE>
+template <bool F16, bool NOISE, bool OUT16>
 __global__ void __launch_bounds__(TailShape::NT)
 clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, int first_tile,
                          const NoiseArgs na) {
@@ -615,7 +659,7 @@ clipped_grad_tail_kernel(const GroupArgs ga, const float* __restrict__ C_all, in
   if (m0 >= ly.d_in || n0 >= ly.d_out) return;       // sub-tile past the layer's edge (whole workgroup)
   const __attribute__((address_space(4))) float* C =
       (const __attribute__((address_space(4))) float*)(uintptr_t)(C_all + ly.c_off);
-  clipped_grad_tile_deep<TailShape, DP_TAIL_DEPTH, F16, NOISE>(ly, ga.B, ga.accumulate, na, l, m0,
+  clipped_grad_tile_deep<TailShape, DP_TAIL_DEPTH, F16, NOISE, OUT16>(ly, ga.B, ga.accumulate, na, l, m0,
                                                                n0, C, lds_tail);
 }
 
@@ -645,11 +689,11 @@ int clipped_grad_big_tail_tiles(int n) {
   return n_tail > DP_TAIL_MAX ? 0 : n_tail;
 }
 
-template <bool F16, bool NOISE>
+template <bool F16, bool NOISE, bool OUT16>
 dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, const NoiseArgs& na,
                                           hipStream_t s) {
-  auto big = clipped_grad_big_kernel<F16, NOISE>;
-  auto tail = clipped_grad_tail_kernel<F16, NOISE>;
+  auto big = clipped_grad_big_kernel<F16, NOISE, OUT16>;
+  auto tail = clipped_grad_tail_kernel<F16, NOISE, OUT16>;
   static ReadyTable ready_big, ready_tail;
   dp_status st0 = allow_big_lds(big, LDS_BYTES, ready_big);
   if (st0 != DP_OK) return st0;
@@ -670,15 +714,21 @@ dp_status launch_clipped_grad_big_group_t(const GroupArgs& ga, const float* C, c
   return hip_status(hipGetLastError());
 }
 
+// out16: the layers' `out` pointers address 16-bit arrays of the operands' storage type.
 dp_status launch_clipped_grad_big_group(const GroupArgs& ga, const float* C, const NoiseArgs* noise,
-                                        hipStream_t s) {
-  if (noise) {
-    return ga.f16 ? launch_clipped_grad_big_group_t<true, true>(ga, C, *noise, s)
-                  : launch_clipped_grad_big_group_t<false, true>(ga, C, *noise, s);
-  }
+                                        hipStream_t s, bool out16) {
   static const NoiseArgs none = {};
-  return ga.f16 ? launch_clipped_grad_big_group_t<true, false>(ga, C, none, s)
-                : launch_clipped_grad_big_group_t<false, false>(ga, C, none, s);
+  const NoiseArgs& na = noise ? *noise : none;
+  switch ((ga.f16 ? 4 : 0) + (noise ? 2 : 0) + (out16 ? 1 : 0)) {
+    case 0: return launch_clipped_grad_big_group_t<false, false, false>(ga, C, na, s);
+    case 1: return launch_clipped_grad_big_group_t<false, false, true>(ga, C, na, s);
+    case 2: return launch_clipped_grad_big_group_t<false, true, false>(ga, C, na, s);
+    case 3: return launch_clipped_grad_big_group_t<false, true, true>(ga, C, na, s);
+    case 4: return launch_clipped_grad_big_group_t<true, false, false>(ga, C, na, s);
+    case 5: return launch_clipped_grad_big_group_t<true, false, true>(ga, C, na, s);
+    case 6: return launch_clipped_grad_big_group_t<true, true, false>(ga, C, na, s);
+    default: return launch_clipped_grad_big_group_t<true, true, true>(ga, C, na, s);
+  }
 }
 
 }  // namespace dpbk

@@ -19,6 +19,10 @@
       clip-weighted gradient's layer shapes: what the vendor's own kernels reach on this device
       for the same flops, without per-sample weights.
 
+  python -m paper_2311_11822_amd.profiling bias-rate
+      times dp_bias_norm (column sums of g over the T tokens + their squared norm) on one
+      layer of each workload's widest output: bytes of g per second.
+
   python -m paper_2311_11822_amd.profiling fill-rate
       compiles csrc/probe_fill_rate.hip and runs it: bytes per second the compute units can pull
       from L2, from the memory-side cache and from HBM.
@@ -107,6 +111,27 @@ def gemm_yardstick() -> None:
         del a, g, out
 
 
+def bias_rate() -> None:
+    import torch
+    from . import binding as dp
+    for name, (B, T, p) in {"cfg4 fc": (4, 2048, 49152), "cfg2 fc": (8, 512, 5120), "cfg1 fc": (16, 256, 3072)}.items():
+        g = (torch.randn(B, T, p, device="cuda") * 0.01).to(torch.bfloat16)
+        colsum = torch.zeros((B, p), dtype=torch.float32, device="cuda")
+        sq = torch.zeros(B, dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            dp.dp_bias_norm(g, dp.DP_BF16, B, T, p, colsum, sq)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            dp.dp_bias_norm(g, dp.DP_BF16, B, T, p, colsum, sq)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        nbytes = 2.0 * B * T * p
+        print(f"{name}: g [{B}, {T}, {p}] bf16 = {nbytes / 1e6:.0f} MB: {ms * 1e3:.1f} us, {nbytes / ms / 1e6:.0f} GB/s", flush=True)
+
+
 def fill_rate() -> None:
     import subprocess
     import tempfile
@@ -122,6 +147,8 @@ def fill_rate() -> None:
 def main() -> None:
     if len(sys.argv) >= 2 and sys.argv[1] == "gemm-yardstick":
         gemm_yardstick()
+    elif len(sys.argv) >= 2 and sys.argv[1] == "bias-rate":
+        bias_rate()
     elif len(sys.argv) >= 2 and sys.argv[1] == "fill-rate":
         fill_rate()
     elif len(sys.argv) >= 2 and sys.argv[1] == "copy":

@@ -597,7 +597,9 @@ def test_cfg2_gpt2_large_full(dp, Pipe):
 
 def test_cfg4_wide_block_shard(dp, Pipe):
     import dataclasses
-    pipe = run_workload(dp, Pipe, "cfg4")
+    # the 12288 x 12288 layer is compared in full (every element, and every 64 x 64 block on its
+    # own); the wider ones on one entry per 64 x 64 block and on random entries
+    pipe = run_workload(dp, Pipe, "cfg4", full_layers=(1,))
     # the shard of rank 2 of 8 crosses the boundary between the second and the third layer
     w = dataclasses.replace(si.WORKLOADS["cfg4"], shard_rank=2)
     off, cnt = w.noise_range()
@@ -1052,6 +1054,84 @@ def test_fused_noise_equals_two_passes(dp, dtype, B, T, dims, gaps, base, accumu
         want = G.reshape(-1)[:n_chk] + sigma * R * z
         have = host(buf).reshape(-1)[:n_chk]
         assert np.all(np.abs(have - want) <= 2e-5 * sigma * R * np.maximum(1.0, np.abs(z)) + 1e-4 * np.abs(G.reshape(-1)[:n_chk]))
+
+
+# ----------------------------------------------------------------------------
+# gradient stored in the 16-bit type of the operands (dp_clipped_grad_noise_multi_h16)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("accumulate", [0, 1])
+@pytest.mark.parametrize("dims", [[(392, 520), (1800, 1544), (128, 136)],      # 63 tiles: 256 x 256-tile kernel
+                                  [(392, 520), (136, 264)]])                    # 8 tiles: sub-tile kernel
+@pytest.mark.parametrize("dtype", HALF_TYPES)
+def test_half_precision_gradient_output(dp, dtype, dims, accumulate):
+    B, T = 3, 96
+    w = si.small_workload("h16", dtype, B, T, dims)
+    layers = gen(w)
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    DT = dt_of(dp, dtype)
+    tdt = torch.bfloat16 if dtype == si.BF16 else torch.float16
+    keep = [(dev(a), dev(g)) for a, g in layers]
+    desc = dp.layer_array([(a, g, T, d, p, 0) for (a, g), (d, p) in zip(keep, dims)])
+    C = np.array([0.7, 0.0, 0.05], dtype=np.float32)
+    Cd = dev(C)
+    offs, acc = [], 4 * 10 ** 8
+    for d, p in dims:
+        offs.append(acc)
+        acc += d * p + 8
+    sigma, R, seed, step = 0.01, 2.0, 5, 9                       # noise of the gradient's own size
+    lo, cnt = offs[0] + 1002, acc - offs[0] - 5000
+    old16 = [(torch.randn(d, p, device="cuda") * 0.05).to(tdt) for d, p in dims]
+    ref32 = [x.float().clone() for x in old16]
+    dp.dp_clipped_grad_noise_multi(desc, DT, B, Cd, ref32, offs, accumulate, lo, cnt, sigma, R, seed, step)
+    got16 = [x.clone() for x in old16]
+    dp.dp_clipped_grad_noise_multi_h16(desc, DT, B, Cd, got16, offs, accumulate, lo, cnt, sigma, R, seed, step)
+    torch.cuda.synchronize()
+    ulp = 2.0 ** -8 if dtype == si.BF16 else 2.0 ** -11       # unit roundoff: largest relative error of one rounding
+    for l, ((a, g), (d, p)) in enumerate(zip(l64, dims)):
+        # the same fp32 value, rounded once to nearest even
+        assert torch.equal(got16[l].view(torch.int16), ref32[l].to(tdt).view(torch.int16)), l
+        # and against the definition: within one unit in the last place of the 16-bit type
+        want = o.clipped_grad(a, g, C.astype(np.float64))
+        if accumulate:
+            want = want + old16[l].float().cpu().numpy().astype(np.float64)
+        z = np.zeros(d * p)
+        x0, x1 = max(offs[l], lo), min(offs[l] + d * p, lo + cnt)
+        z[x0 - offs[l]:x1 - offs[l]] = o.normals(seed, step, x0, x1 - x0)
+        want = want + sigma * R * z.reshape(d, p)
+        have = got16[l].float().cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(have - want) <= ulp * np.abs(want) + 1e-7)
+    # no noise: plain 16-bit weighted gradient
+    plain = [torch.zeros((d, p), dtype=tdt, device="cuda") for d, p in dims]
+    dp.dp_clipped_grad_noise_multi_h16(desc, DT, B, Cd, plain, None, 0, 0, 0, 0.0, 1.0, 0, 0)
+    for l, (a, g) in enumerate(l64):
+        want = o.clipped_grad(a, g, C.astype(np.float64))
+        # (a value next to a rounding boundary may go to the other neighbour: still half a spacing away)
+        # fp16 values below 6.1e-5 are subnormal: spacing 2^-24 whatever their size
+        atol = 1e-9 if dtype == si.BF16 else 2.0 ** -24
+        assert np.all(np.abs(plain[l].float().cpu().numpy() - want) <= ulp * (1 + 1e-3) * np.abs(want) + atol)
+
+
+def test_half_precision_gradient_output_refusals(dp):
+    B, T = 2, 96
+    x = torch.zeros(1 << 20, dtype=torch.int16, device="cuda")
+    p = x.data_ptr()
+    out = torch.zeros(1 << 18, dtype=torch.int16, device="cuda")
+    UNS = dp.DP_ERR_UNSUPPORTED
+    def status(dims, dt, offs, sigma, T=T):
+        desc = dp.layer_array([(p, p, T, d, q, 0) for d, q in dims])
+        try:
+            dp.dp_clipped_grad_noise_multi_h16(desc, dt, B, p, [out] * len(dims), offs, 0, 0, 1 << 30, sigma, 1.0, 0, 0)
+        except dp.DpError as e:
+            return e.status
+        return dp.DP_OK
+    assert status([(72, 264)], dp.DP_BF16, [0], 0.0) == UNS              # narrower than a large tile
+    assert status([(128, 128)], dp.DP_BF16, [0], 0.0, T=50) == UNS       # T not a multiple of 32
+    assert status([(128, 128)], dp.DP_F32, [0], 0.0) == UNS
+    assert status([(128, 128)], dp.DP_F16, [2], 1.0) == UNS              # noise that does not start on a generator block
+    assert status([(128, 128), (72, 264)], dp.DP_BF16, [0, 1 << 20], 1.0) == UNS
+    torch.cuda.synchronize()
+    assert not out.any()
 
 
 # ----------------------------------------------------------------------------
