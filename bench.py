@@ -48,14 +48,20 @@ def workload_flops(w):
 
 
 def ghost_flops_executed(w):
-    """Flops the large-tile ghost-norm kernel issues (it uses the Gram matrices' symmetry): per
-    sample and tile row I of 256 tokens, one 128 x 128 diagonal tile and 256 x 128 tiles for the
-    column blocks J > 2I; each over d + p.  Layers on other kernels count with the nominal figure."""
+    """Flops the ghost-norm kernels issue (they use the Gram matrices' symmetry).  Large-tile
+    kernel: per sample and tile row I of 256 tokens, one 128 x 128 diagonal tile and 256 x 128
+    tiles for the column blocks J > 2I; whole-sample kernel (129 .. 256 tokens): 36 tiles of
+    32 x 32; each over d + p.  Layers on other kernels count with the nominal figure."""
     total = 0.0
     for d, p in w.layers:
         T = w.T
         if 2 * T * T > d * p or T < 96 or d % 64 or p % 64:
             total += 2.0 * w.B * T * T * (d + p) if 2 * T * T <= d * p else 2.0 * w.B * T * d * p
+            continue
+        if 128 < T <= 256:
+            # the whole-sample kernel: the 36 tiles of 32 x 32 on or above the diagonal of the
+            # 8 x 8 tile grid, minus nothing (tiles past T are computed on zeros)
+            total += w.B * 36 * 2.0 * 32 * 32 * (d + p)
             continue
         nj, ni = -(-T // 128), -(-T // 256)
         for I in range(ni):

@@ -35,14 +35,19 @@ bool ghost_uses_big(const dp_layer& ly) {
   return ly.T >= 96 && ghost_big_supports(ly.T, ly.d_in, ly.d_out);
 }
 
+// Samples of 129 .. 256 tokens take the kernel that holds a whole sample in one workgroup.
+bool ghost_uses_sample(const dp_layer& ly) { return ghost_sample_supports(ly.T, ly.d_in, ly.d_out); }
+
 int tiles_per_sample(int path, const dp_layer& ly) {
   if (path == DP_PATH_PEREX) return perex_tiles_per_sample(ly.d_in, ly.d_out);
+  if (ghost_uses_sample(ly)) return 1;
   return ghost_uses_big(ly) ? ghost_big_tiles_per_sample(ly.T) : ghost_tiles_per_sample(ly.T);
 }
 
 // Launches the norm kernels of one path for the listed layers, in chunks of kMaxGroup.
 // part_begin[l] is the layer's first slot in the partial-sum workspace.
-enum NormKernel { kGhostBig = 0, kGhostSmall = 1, kPerex = 2 };
+enum NormKernel { kGhostBig = 0, kGhostSmall = 1, kPerex = 2, kGhostSample = 3 };
+constexpr int kNormKernels = 4;
 
 dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, int n_which,
                         const int64_t* part_begin, dp_dtype dt, int B, float* partials,
@@ -86,9 +91,10 @@ dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, i
       blocks += (int64_t)gl.tiles_per_sample * B;
     }
     ga.total_blocks = (int)blocks;
-    dp_status st = kernel == kGhostBig     ? launch_ghost_big_group(ga, partials, s)
-                   : kernel == kGhostSmall ? launch_ghost_group(ga, partials, s)
-                                           : launch_perex_group(ga, partials, s);
+    dp_status st = kernel == kGhostBig      ? launch_ghost_big_group(ga, partials, s)
+                   : kernel == kGhostSmall  ? launch_ghost_group(ga, partials, s)
+                   : kernel == kGhostSample ? launch_ghost_sample_group(ga, partials, s)
+                                            : launch_perex_group(ga, partials, s);
     if (st != DP_OK) return st;
     st = launch_norm_reduce_group(ga, partials, sqnorm_out, s);
     if (st != DP_OK) return st;
@@ -110,7 +116,7 @@ int64_t norm_slots(const dp_layer* layers, int L, dp_dtype dt, int B, int64_t* b
   return total;
 }
 
-// begin: room for L values; idx: room for 3 L values (the layers of each kernel).  The caller
+// begin: room for L values; idx: room for kNormKernels * L values (the layers of each kernel).  The caller
 // provides both so that this function never touches the heap.  row_of (or nullptr): layer l's
 // squared norms go to row row_of[l] of sqnorm_out instead of row l.
 dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* sqnorm_out, void* ws,
@@ -145,14 +151,17 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
   }
   if (!ws || ws_bytes < (size_t)slots * sizeof(float)) return DP_ERR_WORKSPACE;
   if (!aligned16(ws)) return DP_ERR_INVALID_ARG;
-  int* list[3] = {idx, idx + L, idx + 2 * L};          // kGhostBig, kGhostSmall, kPerex
-  int count[3] = {0, 0, 0};
+  int* list[kNormKernels] = {idx, idx + L, idx + 2 * L, idx + 3 * L};
+  int count[kNormKernels] = {0, 0, 0, 0};
   for (int l = 0; l < L; ++l) {
-    const int k = layers[l].path == DP_PATH_PEREX ? kPerex : ghost_uses_big(layers[l]) ? kGhostBig : kGhostSmall;
+    const int k = layers[l].path == DP_PATH_PEREX ? kPerex
+                  : ghost_uses_sample(layers[l])  ? kGhostSample
+                  : ghost_uses_big(layers[l])     ? kGhostBig
+                                                  : kGhostSmall;
     list[k][count[k]++] = l;
   }
   float* partials = static_cast<float*>(ws);
-  for (int k = 0; k < 3; ++k) {
+  for (int k = 0; k < kNormKernels; ++k) {
     dp_status st = run_norm_path((NormKernel)k, layers, list[k], count[k], begin, dt, B, partials, sqnorm_out, s,
                                  row_of, kept);
     if (st != DP_OK) return st;
@@ -164,7 +173,7 @@ dp_status norms_impl(const dp_layer* layers, int L, dp_dtype dt, int B, float* s
                      size_t ws_bytes, hipStream_t s, const int* row_of = nullptr, float* const* kept = nullptr) {
   if (!layers || L <= 0) return DP_ERR_INVALID_ARG;
   std::vector<int64_t> begin(L);
-  std::vector<int> idx(3 * (size_t)L);
+  std::vector<int> idx(kNormKernels * (size_t)L);
   return norms_impl(layers, L, dt, B, sqnorm_out, ws, ws_bytes, s, begin.data(), idx.data(), row_of, kept);
 }
 
@@ -884,7 +893,7 @@ extern "C" dp_status dp_norms_multi_static(const dp_layer* layers, int L, dp_dty
   // Every partial sum that is read was written by this call's kernels first, so nothing in the
   // array has to start at zero.
   int64_t begin[kStaticMaxLayers];
-  int idx[3 * kStaticMaxLayers];
+  int idx[kNormKernels * kStaticMaxLayers];
   return norms_impl(layers, L, dt, B, sqnorm_out, ws, kStaticScratchBytes, static_cast<hipStream_t>(stream),
                     begin, idx);
 }

@@ -141,6 +141,10 @@ dp_status launch_clipped_grad_group(const GroupArgs& ga, const float* C, hipStre
 int ghost_big_tiles_per_sample(int T);
 bool ghost_big_supports(int T, int d, int p);
 dp_status launch_ghost_big_group(const GroupArgs& ga, float* partials, hipStream_t s);
+// Whole-sample ghost-norm kernel for 129 .. 256 tokens (ghost_sample.hip): one workgroup and one
+// partial sum per sample.
+bool ghost_sample_supports(int T, int d, int p);
+dp_status launch_ghost_sample_group(const GroupArgs& ga, float* partials, hipStream_t s);
 // 256x256-tile kernel with direct global->LDS loads (grad_gemm.hip).
 int clipped_grad_big_tiles(int d, int p);
 // Of a launch of n large tiles, how many (the last ones) go to the sub-tile kernel.
