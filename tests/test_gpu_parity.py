@@ -220,6 +220,10 @@ BF16_SHAPES = [
     (2, 96, 392, 520),       # 6 tiles (sub-tile kernel), sub-tiles wholly past the edge
     (2, 64, 1800, 1544),     # 56 tiles: one short round of 256 x 256 tiles, ragged edges
     (2, 32, 4360, 3848),     # 288 tiles: a full round of large tiles plus 32 tiles of sub-tiles
+    # 129 .. 256 tokens and widths that are multiples of 64: the ghost norm with one workgroup per sample
+    (3, 200, 128, 320),      # ragged T: token rows 200 .. 255 are zero-filled
+    (2, 256, 64, 64),        # one k-block per operand
+    (2, 129, 192, 448),      # one token past the single-tile case
 ]
 
 
