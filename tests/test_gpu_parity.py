@@ -380,8 +380,9 @@ def test_standard_clipping_takes_both_branches(dp, Pipe):
 @pytest.mark.parametrize("with_wide_layer", [False, True])
 def test_stack_with_three_sequence_lengths(dp, Pipe, with_wide_layer):
     # T is a per-layer quantity (section 3: a_l in R^{B x T_l x d_l}); one grouped launch holds
-    # layers of different T.  Ghost norm: layers with T = 96 and 256 ride in a launch that takes
-    # the general plan because of the T = 320 layer; one layer takes the instantiated norm.
+    # layers of different T.  Ghost norm: the T = 96 layer rides in a large-tile launch that takes
+    # the general plan because of the T = 320 layer, the T = 256 layer takes the whole-sample
+    # kernel; one layer takes the instantiated norm.
     # Gradient: 19 tiles (all computed as sub-tiles) or, with the wide T = 64 layer, 75 tiles
     # (all computed as 256 x 256 tiles), k extents 64 to 320 in one launch.
     dims = [(128, 320), (256, 640), (384, 1280), (264, 392)] + ([(1800, 1544)] if with_wide_layer else [])
@@ -1162,7 +1163,7 @@ def fp16_path_check(dp, Pipe, w, tol_norm=TOL_BF16_NORM):
 
 
 def test_fp16_gpt_block_stack(dp, Pipe):
-    # one GPT-shaped block (d = 256) at T = 256: large-tile gradient kernel, compact ghost plan,
+    # one GPT-shaped block (d = 256) at T = 256: large-tile gradient kernel, whole-sample ghost norm,
     # and the instantiated norm on the square layer
     w = si.small_workload("h", si.F16, 4, 256, [(256, 768), (256, 256), (256, 1024), (1024, 256)],
                           clip_mode=si.CLIP_AUTOMATIC)
