@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdp_bk.so")
-SOURCES = ["dp_api.hip", "noise.hip", "clip.hip", "fp32_kernels.hip", "ghost.hip", "tn_gemm.hip", "grad_gemm.hip", "ghost_big.hip", "bias.hip", "layerwise.hip", "kept.hip", "ghost_sample.hip"]
+SOURCES = ["dp_api.hip", "noise.hip", "clip.hip", "fp32_kernels.hip", "ghost.hip", "tn_gemm.hip", "grad_gemm.hip", "ghost_big.hip", "bias.hip", "layerwise.hip", "kept.hip", "ghost_sample.hip", "perex_dma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

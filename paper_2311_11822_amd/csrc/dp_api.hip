@@ -13,6 +13,10 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+#ifndef DP_PEREX_DMA
+#define DP_PEREX_DMA true
+#endif
+
 bool dtype_ok(dp_dtype dt) { return dt == DP_F32 || dt == DP_BF16 || dt == DP_F16; }
 
 bool dims_ok(dp_dtype dt, int B, int T, int d, int p) {
@@ -91,9 +95,15 @@ dp_status run_norm_path(NormKernel kernel, const dp_layer* layers, int* which, i
       blocks += (int64_t)gl.tiles_per_sample * B;
     }
     ga.total_blocks = (int)blocks;
+    // instantiated norm: the kernel with the deep load pipeline unless a slab is beyond its
+    // 32-bit addressing (both use the same tiles and partial-sum slots)
+    bool dma = DP_PEREX_DMA;
+    for (int j = 0; j < ga.n_layers; ++j)
+      dma = dma && perex_dma_supports(ga.layer[j].T, ga.layer[j].d_in, ga.layer[j].d_out);
     dp_status st = kernel == kGhostBig      ? launch_ghost_big_group(ga, partials, s)
                    : kernel == kGhostSmall  ? launch_ghost_group(ga, partials, s)
                    : kernel == kGhostSample ? launch_ghost_sample_group(ga, partials, s)
+                   : dma                    ? launch_perex_dma_group(ga, partials, s)
                                             : launch_perex_group(ga, partials, s);
     if (st != DP_OK) return st;
     st = launch_norm_reduce_group(ga, partials, sqnorm_out, s);

@@ -134,6 +134,9 @@ int perex_tiles_per_sample(int d, int p);
 int clipped_grad_tiles(int d, int p);
 dp_status launch_ghost_group(const GroupArgs& ga, float* partials, hipStream_t s);
 dp_status launch_perex_group(const GroupArgs& ga, float* partials, hipStream_t s);
+// Same tiles and partial-sum slots with direct global->LDS loads, three k-blocks ahead (perex_dma.hip).
+bool perex_dma_supports(int T, int d, int p);
+dp_status launch_perex_dma_group(const GroupArgs& ga, float* partials, hipStream_t s);
 dp_status launch_norm_reduce_group(const GroupArgs& ga, const float* partials, float* sqnorm_out,
                                    hipStream_t s);
 dp_status launch_clipped_grad_group(const GroupArgs& ga, const float* C, hipStream_t s);

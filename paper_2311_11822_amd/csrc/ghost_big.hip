@@ -23,13 +23,12 @@
 #include <type_traits>
 
 #include "dp_internal.h"
+#include "lds_dma.h"
 #include "tile_order.h"
 
 namespace dpbk {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr int TI = 256, TJ = 128, BK = 64;
 constexpr int NT = 256;
@@ -48,33 +47,9 @@ struct Plan {
 };
 constexpr int LOADS_I = 8, LOADS_J = 4;              // per wave per k-block (a wave-load = 8 rows)
 
-__device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
-  const uint64_t p = reinterpret_cast<uint64_t>(base);
-  i32x4 r;
-  r[0] = (int)(uint32_t)p;
-  r[1] = (int)(uint32_t)(p >> 32) & 0xFFFF;          // stride 0: raw buffer
-  r[2] = (int)bytes;
-  r[3] = 0x00020000;
-  return r;
-}
-
-// 16 bytes per lane from buffer `rsrc` at byte voff + soff to LDS at lds_base + 16*lane.
-// The range check sees voff: a lane whose voff is past the descriptor's size fetches zeros.
-__device__ __forceinline__ void load_to_lds(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
-  asm volatile(
-      "s_mov_b32 m0, %0\n\t"
-      "s_nop 0\n\t"
-      "buffer_load_dwordx4 %1, %2, %3 offen lds"
-      :
-      : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
-      : "memory", "m0");
-}
-
 __device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
   return *(__attribute__((address_space(3))) bf16x8*)(uintptr_t)addr;
 }
-
-#define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
 // After which MFMA of a k-step (2 MI MFMAs) load x of its per_ks global->LDS loads is issued.
 constexpr int load_slot(int mi, int per_ks, int x) {

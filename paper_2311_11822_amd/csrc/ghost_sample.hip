@@ -18,12 +18,11 @@
 #include <type_traits>
 
 #include "dp_internal.h"
+#include "lds_dma.h"
 
 namespace dpbk {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr int ROWS = 256, BK = 64;
 constexpr int NW = 8, NT = 64 * NW;
@@ -33,33 +32,9 @@ constexpr int NSTAGE = 5;
 constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;       // 160 KiB
 constexpr int LOADS = ROWS / 8 / NW;                  // wave-loads (8 rows each) per wave and k-block: 4
 
-__device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
-  const uint64_t p = reinterpret_cast<uint64_t>(base);
-  i32x4 r;
-  r[0] = (int)(uint32_t)p;
-  r[1] = (int)(uint32_t)(p >> 32) & 0xFFFF;           // stride 0: raw buffer
-  r[2] = (int)bytes;
-  r[3] = 0x00020000;
-  return r;
-}
-
-// 16 bytes per lane from buffer `rsrc` at byte voff + soff to LDS at lds_base + 16*lane.
-// The range check sees voff: a lane whose voff is past the descriptor's size fetches zeros.
-__device__ __forceinline__ void load_to_lds(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
-  asm volatile(
-      "s_mov_b32 m0, %0\n\t"
-      "s_nop 0\n\t"
-      "buffer_load_dwordx4 %1, %2, %3 offen lds"
-      :
-      : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
-      : "memory", "m0");
-}
-
 __device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
   return *(__attribute__((address_space(3))) bf16x8*)(uintptr_t)addr;
 }
-
-#define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
 template <bool F16>
 __global__ void __launch_bounds__(NT)

@@ -26,6 +26,7 @@
 #include <type_traits>
 
 #include "dp_internal.h"
+#include "lds_dma.h"
 #include "tile_order.h"
 #include "tn_tile.h"
 
@@ -33,7 +34,6 @@ namespace dpbk {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4v;
 
 #ifndef DP_GRAD_NSTAGE
@@ -46,30 +46,6 @@ constexpr int TILE_BYTES = BK * ROW_BYTES;             // one operand, one stage
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;            // 32 KiB
 constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;        // 160 KiB with 5 stages: all of the CU's LDS
 constexpr int LOADS = BK / 8;                          // per operand per thread per k-block
-constexpr unsigned OOB = 0x80000000u;
-
-__device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
-  const uint64_t p = reinterpret_cast<uint64_t>(base);
-  i32x4 r;
-  r[0] = (int)(uint32_t)p;
-  r[1] = (int)(uint32_t)(p >> 32) & 0xFFFF;            // stride 0: raw buffer
-  r[2] = (int)bytes;
-  r[3] = 0x00020000;
-  return r;
-}
-
-// 16 bytes per lane from buffer `rsrc` at byte `voff` to LDS at lds_base + 16*lane.
-// The lane's byte address is voff + soff; the range check sees voff, so a lane whose voff has
-// bit 31 set (>= any slab size) fetches zeros whatever soff is.
-__device__ __forceinline__ void load_to_lds(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
-  asm volatile(
-      "s_mov_b32 m0, %0\n\t"
-      "s_nop 0\n\t"
-      "buffer_load_dwordx4 %1, %2, %3 offen lds"
-      :
-      : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
-      : "memory", "m0");
-}
 
 __device__ __forceinline__ s16x4 lds_read_tr(unsigned addr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -82,8 +58,6 @@ struct Frag {
     bf16x8 v;
   };
 };
-
-#define DP_PIN() __builtin_amdgcn_sched_barrier(0)
 
 // Tile t of the launch -> layer and tile origin (order inside a layer: tile_order.h).
 __device__ __forceinline__ void locate_tile(const GroupArgs& ga, int t, int& layer, int& m0, int& n0) {
@@ -462,7 +436,6 @@ clipped_grad_big_kernel(const GroupArgs ga, const float* __restrict__ C_global, 
   else
     store_tile(std::false_type{});
 }
-
 
 // ---------------------------------------------------------------------------------
 // Tail of a launch.  All tiles of a launch take the same time and one workgroup fills a compute

@@ -10,6 +10,15 @@ namespace dpbk {
 __host__ __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 __host__ __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
 
+// Workgroup id -> work item such that every XCD takes a contiguous eighth of the items:
+// workgroup b runs on XCD b % 8 (round-robin dispatch), and XCD x gets items
+// [start_x, start_x + n_x) in the order its workgroups are dispatched.  Items that share operand
+// panels are numbered consecutively by the callers, so they meet in one XCD's L2.
+__host__ __device__ __forceinline__ int contiguous_eighth(int block, int total) {
+  const int per = total >> 3, rest = total & 7, xcd = block & 7, idx = block >> 3;
+  return xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx;
+}
+
 // ---------------------------------------------------------------------------------
 // Clip-weighted gradient: 256 x 256 tiles of the [d_in, d_out] gradient.  Tile number `rem` of a
 // layer with tiles_m x tiles_n tiles -> tile row and column.  32 consecutive numbers form a patch
@@ -39,9 +48,7 @@ __host__ __device__ __forceinline__ void grad_tile_of(int tiles_m, int tiles_n, 
 __host__ __device__ __forceinline__ int grad_logical_tile(int block, int total) {
   constexpr int ROUND = 256;
   const int base = (block / ROUND) * ROUND, q = block - base;
-  const int n = imin(ROUND, total - base);
-  const int per = n >> 3, rest = n & 7, xcd = q & 7, idx = q >> 3;
-  return base + (xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx);
+  return base + contiguous_eighth(q, imin(ROUND, total - base));
 }
 
 // ---------------------------------------------------------------------------------
@@ -86,8 +93,7 @@ __host__ __device__ __forceinline__ int ghost_logical_tile(int block, int total)
   const int xcd = qd & 7, idx = qd >> 3;
   if (base + ROUND <= total) return base + ((xcd - round) & 7) * CHUNK + idx;
   // last, partial round: contiguous eighths
-  const int m = total - base, per = m >> 3, rest = m & 7;
-  return base + (xcd < rest ? xcd * (per + 1) + idx : rest * (per + 1) + (xcd - rest) * per + idx);
+  return base + contiguous_eighth(qd, total - base);
 }
 
 }  // namespace dpbk

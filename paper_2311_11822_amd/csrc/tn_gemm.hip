@@ -14,6 +14,7 @@
 // register file cannot hold two at these tile sizes, and the re-expression adds only B fp32
 // roundings per output.
 #include "dp_internal.h"
+#include "tile_order.h"
 #include "tn_tile.h"
 
 namespace dpbk {
@@ -45,9 +46,12 @@ template <class S, bool F16>
 __global__ void __launch_bounds__(S::NT)
 perex_norm_kernel(const GroupArgs ga, float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  const int l = find_layer(ga, blockIdx.x);
+  // The tiles of one (layer, sample) read the same panels of a_i and g_i: numbered consecutively
+  // and dealt to the XCDs in contiguous eighths, they share them through one L2.
+  const int item = contiguous_eighth(blockIdx.x, ga.total_blocks);
+  const int l = find_layer(ga, item);
   const GroupLayer& ly = ga.layer[l];
-  const int local = blockIdx.x - ly.tile_begin;
+  const int local = item - ly.tile_begin;
   const int sample = local / ly.tiles_per_sample;
   const int tile = local % ly.tiles_per_sample;
   const int tiles_n = (ly.d_out + S::BN - 1) / S::BN;
