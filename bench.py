@@ -32,6 +32,7 @@ import synth_inputs as si  # noqa: E402
 
 PEAK_BF16_FLOPS = 2.5e15       # MI355X dense bf16 MFMA
 PEAK_HBM_BYTES = 8.0e12
+NOISE_ALU_PEAK_BLOCKS = 256 * 4 * 64 * 2.4e9 / 690      # Philox4x32-10 + Box-Muller blocks/s the vector ALUs can issue
 HEADLINE = "cfg4"
 
 
@@ -243,7 +244,11 @@ def measure(name, args, torch, BkPipeline, noise_pass=False):
         gbps = 8.0 * cnt / (ms.mean() * 1e-3) / 1e9
         res["noise_pass"] = {"kernel": "noise_bulk_kernel", "elements": cnt, "bytes": 8 * cnt,
                              "ms": float(ms.mean()), "ms_min": float(ms.min()),
-                             "gbps": gbps, "frac_hbm_peak": gbps * 1e9 / PEAK_HBM_BYTES}
+                             "gbps": gbps, "frac_hbm_peak": gbps * 1e9 / PEAK_HBM_BYTES,
+                             # the generator's instruction stream is ~690 vector-ALU clocks per
+                             # 4-element block and wave: 256 CUs x 4 SIMDs x 64 lanes x 2.4 GHz / 690
+                             "gblocks_per_s": cnt / 4 / (ms.mean() * 1e-3) / 1e9,
+                             "frac_alu_peak": cnt / 4 / (ms.mean() * 1e-3) / NOISE_ALU_PEAK_BLOCKS}
     del pipe, layers
     gc.collect()
     torch.cuda.empty_cache()
