@@ -313,6 +313,10 @@ dp_status dp_clipped_grad_kept_multi(const dp_layer* layers, int L, dp_dtype dt,
  * path (path == DP_PATH_PEREX, 16-bit storage) whose whole gradient fits one workgroup tile (up to
  * 128 x 128, 512 x 32 or 32 x 512) is done in ONE kernel that reads a and g once: per sample it
  * forms G_i = a_i^T g_i in registers, takes ||G_i||, C_i = clip(||G_i||; R_l) and adds C_i G_i.
+ * A larger layer on the instantiated path keeps its G_i ([B, d_in, d_out] fp32) in the workspace
+ * between its norm kernel and a weighted sum, as dp_norms_multi_keep + dp_clipped_grad_kept_multi
+ * do, so its a and g are read once as well; layers are given room in stack order up to 2 GiB in
+ * total, the rest contract a and g a second time.
  * The result is that of dp_norms_multi + dp_clip_factors_grouped (one group per layer)
  * + dp_clipped_grad_grouped + dp_add_noise with R = dp_group_noise_threshold(R, L):
  *   grads[l] (+)= sum_i C[l,i] a_{l,i}^T g_{l,i} + sigma ||(R_1..R_L)||_2 z   on the shard's elements.

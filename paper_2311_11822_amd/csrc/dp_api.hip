@@ -395,6 +395,68 @@ dp_status clipped_grad_impl(const dp_layer* layers, int L, dp_dtype dt, int B, c
   return DP_OK;
 }
 
+// Sum_i C_i G_i from kept per-sample gradients for the layers that have them (kept[l] != nullptr),
+// up to kMaxGroup layers per launch.  c_off (or nullptr): layer l's weights are C[c_off[l] + i].
+// noise (or nullptr): added by the same kernel when the layer starts on a generator block, else
+// by a pass afterwards.
+dp_status kept_sum_impl(const dp_layer* layers, int L, int B, const float* C, const int* c_off,
+                        float* const* kept, float* const* grads, const NoiseSpec* noise, int accumulate,
+                        hipStream_t s) {
+  const bool noisy = noise != nullptr && noise->stddev > 0.f;
+  NoiseArgs na = {};
+  if (noisy) {
+    na.stddev = noise->stddev;
+    na.step_lo = (uint32_t)noise->step;
+    na.step_hi = (uint32_t)(noise->step >> 32);
+    na.lo = noise->lo;
+    na.hi = noise->hi;
+    na.rk = make_round_keys(noise->seed);
+  }
+  int l = 0;
+  while (l < L) {
+    GroupArgs ga;
+    ga.B = B;
+    ga.accumulate = accumulate;
+    ga.f16 = 0;
+    ga.n_layers = 0;
+    int64_t blocks = 0;
+    int members[kMaxGroup];
+    for (; l < L && ga.n_layers < kMaxGroup; ++l) {
+      if (!kept || !kept[l]) continue;
+      const int nb = kept_blocks(layers[l].d_in, layers[l].d_out);
+      if (ga.n_layers > 0 && blocks + nb > INT32_MAX / 2) break;
+      GroupLayer& gl = ga.layer[ga.n_layers];
+      gl.a = kept[l];
+      gl.g = nullptr;
+      gl.out = grads[l];
+      gl.T = layers[l].T;
+      gl.d_in = layers[l].d_in;
+      gl.d_out = layers[l].d_out;
+      gl.path = DP_PATH_PEREX;
+      gl.tile_begin = (int)blocks;
+      gl.sq_index = l;
+      gl.part_begin = 0;
+      gl.tiles_per_sample = nb;
+      gl.c_off = c_off ? c_off[l] : 0;
+      na.layer_off[ga.n_layers] =
+          noisy && (noise->grad_offset[l] & 3) == 0 ? noise->grad_offset[l] : ~(uint64_t)0;
+      members[ga.n_layers] = l;
+      blocks += nb;
+      ++ga.n_layers;
+    }
+    if (ga.n_layers == 0) break;
+    ga.total_blocks = (int)blocks;
+    dp_status st = launch_kept_weighted_sum(ga, C, na, s);
+    if (st != DP_OK) return st;
+    for (int j = 0; j < ga.n_layers; ++j)
+      if (noisy && na.layer_off[j] == ~(uint64_t)0) {
+        st = noise_after(noise, members[j], layers[members[j]], grads[members[j]], s);
+        if (st != DP_OK) return st;
+      }
+  }
+  return DP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -608,57 +670,8 @@ dp_status dp_clipped_grad_kept_multi(const dp_layer* layers, int L, dp_dtype dt,
                            noisy ? &sub_spec : nullptr);
     if (st != DP_OK) return st;
   }
-  // (2) layers with kept gradients: weighted sums, up to kMaxGroup layers per launch
-  NoiseArgs na = {};
-  na.stddev = spec.stddev;
-  na.step_lo = (uint32_t)step;
-  na.step_hi = (uint32_t)(step >> 32);
-  na.lo = spec.lo;
-  na.hi = spec.hi;
-  na.rk = make_round_keys(seed);
-  int l = 0;
-  while (l < L) {
-    GroupArgs ga;
-    ga.B = B;
-    ga.accumulate = accumulate;
-    ga.f16 = 0;
-    ga.n_layers = 0;
-    int64_t blocks = 0;
-    int members[kMaxGroup];
-    for (; l < L && ga.n_layers < kMaxGroup; ++l) {
-      if (!kept || !kept[l]) continue;
-      const int nb = kept_blocks(layers[l].d_in, layers[l].d_out);
-      if (ga.n_layers > 0 && blocks + nb > INT32_MAX / 2) break;
-      GroupLayer& gl = ga.layer[ga.n_layers];
-      gl.a = kept[l];
-      gl.g = nullptr;
-      gl.out = grads[l];
-      gl.T = layers[l].T;
-      gl.d_in = layers[l].d_in;
-      gl.d_out = layers[l].d_out;
-      gl.path = DP_PATH_PEREX;
-      gl.tile_begin = (int)blocks;
-      gl.sq_index = l;
-      gl.part_begin = 0;
-      gl.tiles_per_sample = nb;
-      gl.c_off = 0;
-      // the kernel adds the noise when the layer starts on a generator block; else a pass afterwards
-      na.layer_off[ga.n_layers] = noisy && (grad_offset[l] & 3) == 0 ? grad_offset[l] : ~(uint64_t)0;
-      members[ga.n_layers] = l;
-      blocks += nb;
-      ++ga.n_layers;
-    }
-    if (ga.n_layers == 0) break;
-    ga.total_blocks = (int)blocks;
-    st = launch_kept_weighted_sum(ga, C, na, s);
-    if (st != DP_OK) return st;
-    for (int j = 0; j < ga.n_layers; ++j)
-      if (noisy && na.layer_off[j] == ~(uint64_t)0) {
-        st = noise_after(&spec, members[j], layers[members[j]], grads[members[j]], s);
-        if (st != DP_OK) return st;
-      }
-  }
-  return DP_OK;
+  // (2) layers with kept gradients: weighted sums
+  return kept_sum_impl(layers, L, B, C, nullptr, kept, grads, noisy ? &spec : nullptr, accumulate, s);
 }
 
 }  // extern "C"
@@ -681,16 +694,29 @@ struct FusedPlan {
   int n_fused = 0;
   int chunks = 1;                // sample chunks per fused layer
   int64_t floats = 0;            // partial sums of all fused layers
+  // Other layers on the instantiated path keep their per-sample gradients G_i between the norm and
+  // the weighted sum (as dp_norms_multi_keep does): float offset of layer l's [B, d, p] block in
+  // the kept region of the workspace, or -1.  Layers are taken in order while the region stays
+  // within kKeptMaxBytes; the rest contract a and g a second time.
+  std::vector<int64_t> kept_off;
+  int64_t kept_floats = 0;
 };
+constexpr int64_t kKeptMaxBytes = (int64_t)2 << 30;
 
 FusedPlan plan_fused(const dp_layer* layers, int L, dp_dtype dt, int B) {
   FusedPlan fp;
   fp.shape.assign(L, -1);
+  fp.kept_off.assign(L, -1);
   if (dt == DP_F32) return fp;
   for (int l = 0; l < L; ++l)
     if (layers[l].path == DP_PATH_PEREX) {
       fp.shape[l] = layerwise_fused_shape(layers[l].d_in, layers[l].d_out);
       fp.n_fused += fp.shape[l] >= 0;
+      const int64_t n = (int64_t)B * layers[l].d_in * layers[l].d_out;
+      if (fp.shape[l] < 0 && n <= INT32_MAX - 4096 && (fp.kept_floats + n) * 4 <= kKeptMaxBytes) {
+        fp.kept_off[l] = fp.kept_floats;
+        fp.kept_floats += (n + 3) & ~(int64_t)3;                  // blocks stay 16-byte aligned
+      }
     }
   if (fp.n_fused == 0) return fp;
   // enough workgroups to fill the 256 compute units when the batch allows
@@ -713,7 +739,7 @@ size_t dp_layerwise_workspace_bytes(const dp_layer* layers, int L, dp_dtype dt, 
   if (norms == 0) return 0;
   const FusedPlan fp = plan_fused(layers, L, dt, B);
   if (fp.floats > INT32_MAX) return 0;
-  return align16(norms) + (size_t)fp.floats * sizeof(float);
+  return align16(norms) + align16((size_t)fp.floats * sizeof(float)) + (size_t)fp.kept_floats * sizeof(float);
 }
 
 dp_status dp_layerwise_clipped_grad(const dp_layer* layers, int L, dp_dtype dt, int B, const float* R,
@@ -755,6 +781,8 @@ dp_status dp_layerwise_clipped_grad(const dp_layer* layers, int L, dp_dtype dt, 
   const FusedPlan fp = plan_fused(layers, L, dt, B);
   float* fused_partial = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) +
                                                   align16(dp_norms_multi_workspace_bytes(layers, L, dt, B)));
+  float* kept_region = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(fused_partial) +
+                                                align16((size_t)fp.floats * sizeof(float)));
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   NoiseArgs na = {};
@@ -822,10 +850,12 @@ dp_status dp_layerwise_clipped_grad(const dp_layer* layers, int L, dp_dtype dt, 
       }
     }
     // (2) the other layers of the pass: norms, clip factors, weighted gradients
+    //     (instantiated layers keep G_i in the workspace: their gradient is sum_i C_i G_i)
     std::vector<dp_layer> sub;
     std::vector<int> row, c_off;
-    std::vector<float*> sub_grads;
+    std::vector<float*> sub_grads, sub_kept;
     std::vector<uint64_t> sub_off;
+    bool any_kept = false;
     for (int l = l0; l < l1; ++l)
       if (fp.shape[l] < 0) {
         sub.push_back(layers[l]);
@@ -833,10 +863,13 @@ dp_status dp_layerwise_clipped_grad(const dp_layer* layers, int L, dp_dtype dt, 
         c_off.push_back(l * B);
         sub_grads.push_back(grads[l]);
         sub_off.push_back(noisy ? grad_offset[l] : 0);
+        sub_kept.push_back(fp.kept_off[l] >= 0 ? kept_region + fp.kept_off[l] : nullptr);
+        any_kept = any_kept || fp.kept_off[l] >= 0;
       }
     if (!sub.empty()) {
       const int n = (int)sub.size();
-      dp_status st = norms_impl(sub.data(), n, dt, B, sqnorm_out, ws, ws_bytes, s, row.data());
+      dp_status st = norms_impl(sub.data(), n, dt, B, sqnorm_out, ws, ws_bytes, s, row.data(),
+                                any_kept ? sub_kept.data() : nullptr);
       if (st != DP_OK) return st;
       std::vector<int32_t> begin(l1 - l0 + 1);
       for (int l = l0; l <= l1; ++l) begin[l - l0] = l;
@@ -850,9 +883,30 @@ dp_status dp_layerwise_clipped_grad(const dp_layer* layers, int L, dp_dtype dt, 
       spec.stddev = stddev;
       spec.seed = seed;
       spec.step = step;
-      st = clipped_grad_impl(sub.data(), n, dt, B, C_out, c_off.data(), sub_grads.data(), accumulate, stream,
-                             noisy ? &spec : nullptr);
-      if (st != DP_OK) return st;
+      // layers without kept gradients: the contraction over a and g
+      std::vector<dp_layer> rest;
+      std::vector<int> rest_c;
+      std::vector<float*> rest_grads;
+      std::vector<uint64_t> rest_off;
+      for (int j = 0; j < n; ++j)
+        if (!sub_kept[j]) {
+          rest.push_back(sub[j]);
+          rest_c.push_back(c_off[j]);
+          rest_grads.push_back(sub_grads[j]);
+          rest_off.push_back(sub_off[j]);
+        }
+      if (!rest.empty()) {
+        NoiseSpec rest_spec = spec;
+        rest_spec.grad_offset = rest_off.data();
+        st = clipped_grad_impl(rest.data(), (int)rest.size(), dt, B, C_out, rest_c.data(), rest_grads.data(),
+                               accumulate, stream, noisy ? &rest_spec : nullptr);
+        if (st != DP_OK) return st;
+      }
+      if (any_kept) {
+        st = kept_sum_impl(sub.data(), n, B, C_out, c_off.data(), sub_kept.data(), sub_grads.data(),
+                           noisy ? &spec : nullptr, accumulate, s);
+        if (st != DP_OK) return st;
+      }
     }
     l0 = l1;
   }

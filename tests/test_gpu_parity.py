@@ -930,12 +930,13 @@ def test_layerwise_without_book_keeping(dp, Pipe, dtype, mode, stability):
         pipe.flat.fill_(-1.0)
         pipe.layerwise_step(mode, stability, 0.0, seed, step, 0, psi, layers_per_pass=per_pass)
         np.testing.assert_array_equal(host(pipe.flat), clean)
-    # the layers the grouped kernels compute give the bits of the two-pass sequence
+    # the ghost-path layer gives the bits of the two-pass sequence (layer 4, on the instantiated
+    # path, is the weighted sum of its kept per-sample gradients here and a second contraction there)
     pipe.norms()
     pipe.clip_grouped(mode, stability)
     pipe.flat.fill_(3.0)
     pipe.grad_grouped()
-    for l in (4, 5):
+    for l in (5,):
         np.testing.assert_array_equal(host(pipe.grads[l]).reshape(-1), clean[sum(d * p for d, p in dims[:l]):][:dims[l][0] * dims[l][1]])
     # accumulate, and noise of level sigma ||R||_2 on a shard that starts and ends inside layers
     lo, cnt = 1000, psi - 1500
