@@ -422,6 +422,75 @@ def test_stack_with_three_sequence_lengths(dp, Pipe, with_wide_layer):
     assert np.all(np.abs(have - want) <= 2e-5 * sigma * R * np.maximum(1.0, np.abs(z)) + 1e-4 * np.abs(want - sigma * R * z))
 
 
+def random_stack(seed):
+    """A seeded stack of four layers whose (T, d, p) are drawn so that the sweep reaches every
+    16-bit kernel: whole and ragged k-blocks, widths from 8 up, both norm paths."""
+    rng = np.random.default_rng(seed)
+    B = int(rng.integers(1, 6))
+    dims, Ts = [], []
+    for _ in range(4):
+        kind = int(rng.integers(0, 4))
+        if kind == 0:        # whole 32-token blocks and wide layers: large-tile kernels
+            T = 32 * int(rng.integers(1, 11))
+            d, p = (8 * int(rng.integers(16, 90)) for _ in range(2))
+        elif kind == 1:      # widths that are multiples of 64: large-tile / whole-sample ghost norm
+            T = int(rng.integers(96, 330))
+            d, p = (64 * int(rng.integers(1, 9)) for _ in range(2))
+        elif kind == 2:      # anything goes
+            T = int(rng.integers(1, 300))
+            d, p = (8 * int(rng.integers(1, 60)) for _ in range(2))
+        else:                # long samples, narrow layers: the instantiated path
+            T = int(rng.integers(200, 700))
+            d, p = (8 * int(rng.integers(1, 40)) for _ in range(2))
+        dims.append((d, p))
+        Ts.append(T)
+    return B, Ts, dims
+
+
+@pytest.mark.parametrize("dtype", HALF_TYPES)
+@pytest.mark.parametrize("seed", range(16))
+def test_random_stacks(dp, Pipe, seed, dtype):
+    B, Ts, dims = random_stack(seed)
+    layers = []
+    for l, ((d, p), T) in enumerate(zip(dims, Ts)):
+        w = si.small_workload("rs", dtype, B, T, [(d, p)], data_seed=1000 * seed + l)
+        layers.append(si.gen_layer(w, 0))
+    l64 = [(si.to_f64(a), si.to_f64(g)) for a, g in layers]
+    sqn = np.stack([o.perex_sqnorm(a, g) for a, g in l64])
+    for keep in (True, False):
+        pipe = Pipe([(dev(a), dev(g)) for a, g in layers], keep_instantiated=keep)
+        assert pipe.paths == [o.choose_path(T, d, p) for T, (d, p) in zip(Ts, dims)]
+        pipe.norms()
+        pipe.clip(dp.DP_CLIP_AUTOMATIC, 1.0, 0.01)
+        pipe.flat.fill_(7.0)
+        pipe.grad()
+        assert rel(host(pipe.sqnorm), sqn) <= TOL_BF16_NORM, (B, Ts, dims)
+        C, _ = o.clip_factors(sqn, o.CLIP_AUTOMATIC, 1.0, 0.01)
+        assert rel(host(pipe.C), C) <= TOL_BF16_NORM
+        Cg = host(pipe.C).astype(np.float64)
+        for l, (a, g) in enumerate(l64):
+            assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, Cg)) <= 1e-5, (l, B, Ts, dims)
+        # noise in the gradient pass = gradient pass + noise pass, on a shard inside the stack
+        lo, cnt = pipe.psi // 7, pipe.psi // 2
+        two_pass = pipe.flat.clone()
+        dp.dp_add_noise(two_pass[lo:], lo, cnt, 0.7, 1.0, 5 + seed, 2)
+        pipe.flat.fill_(-3.0)
+        pipe.grad_noise(0.7, 1.0, 5 + seed, 2, lo, cnt)
+        assert torch.equal(pipe.flat, two_pass)
+    # layer-wise clipping pass by pass against the oracle's grouped definition
+    L = len(dims)
+    R = [0.3, 1.0, 0.1, 2.0]
+    pipe.set_groups(list(range(L)), R)
+    pipe.flat.fill_(2.0)
+    pipe.layerwise_step(dp.DP_CLIP_STANDARD, 0.01, 0.0, 1, 1, 0, pipe.psi)
+    ref = o.private_gradient_grouped(l64, list(range(L)), R, o.CLIP_STANDARD, 0.0, 0.01, 1, 1, 0, 0)
+    assert rel(host(pipe.sqnorm), ref["sqnorm"]) <= TOL_BF16_NORM
+    Cl = host(pipe.C_groups).astype(np.float64)
+    assert rel(Cl, ref["C"]) <= TOL_BF16_NORM
+    for l, (a, g) in enumerate(l64):
+        assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, Cl[l])) <= 1e-5, (l, B, Ts, dims)
+
+
 @pytest.mark.parametrize("B,T,d,p", [
     (6, 64, 1800, 1544),     # one short round of 256 x 256 tiles
     (6, 96, 392, 520),       # sub-tile kernel only
