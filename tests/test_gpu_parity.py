@@ -422,6 +422,37 @@ def test_stack_with_three_sequence_lengths(dp, Pipe, with_wide_layer):
     assert np.all(np.abs(have - want) <= 2e-5 * sigma * R * np.maximum(1.0, np.abs(z)) + 1e-4 * np.abs(want - sigma * R * z))
 
 
+@pytest.mark.parametrize("d", [465920, 524288])
+def test_sample_slabs_at_the_addressing_limit(dp, d):
+    # The kernels that load through buffer descriptors address a sample's [T, d] slab with 32-bit
+    # byte offsets.  d = 465920: (T + 256) d 2 bytes lies just below 2^31, the largest slab those
+    # kernels take; d = 524288: T d 2 = 2^31 exactly, so every kernel falls back to its 64-bit
+    # form.  Two samples, so that the second slab starts 2 GiB into the array.  Inputs are drawn
+    # on the device (seeded; a ~ N(0,1), g ~ N(0, 1e-4) as in the workloads) and the oracle runs on
+    # column chunks of a: rows of G and the sum of squares split exactly over them.
+    B, T, p = 2, 2048, 128
+    gen_ = torch.Generator(device="cuda").manual_seed(d)
+    a = torch.randn(B, T, d, device="cuda", generator=gen_).to(torch.bfloat16)
+    g = (torch.randn(B, T, p, device="cuda", generator=gen_) * 1e-2).to(torch.bfloat16)
+    C = np.array([0.75, 0.031], dtype=np.float32)
+    g64 = g.float().cpu().numpy().astype(np.float64)
+    want_sq = np.zeros(B)
+    want_G = np.empty((d, p))
+    step = 16384
+    for j0 in range(0, d, step):
+        a64 = a[:, :, j0:j0 + step].float().cpu().numpy().astype(np.float64)
+        want_sq += o.perex_sqnorm(a64, g64)
+        want_G[j0:j0 + step] = o.clipped_grad(a64, g64, C.astype(np.float64))
+    for path, fn in ((dp.DP_PATH_GHOST, dp.dp_ghost_norm), (dp.DP_PATH_PEREX, dp.dp_perex_norm)):
+        ws = torch.empty(dp.dp_norm_workspace_bytes(path, dp.DP_BF16, B, T, d, p), dtype=torch.uint8, device="cuda")
+        out = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
+        fn(a, g, dp.DP_BF16, B, T, d, p, out, ws)
+        assert rel(host(out), want_sq) <= TOL_BF16_NORM, (path, host(out), want_sq)
+    grad = torch.full((d, p), 3.0, dtype=torch.float32, device="cuda")
+    dp.dp_clipped_grad(a, g, dp.DP_BF16, B, T, d, p, dev(C), grad, 0)
+    assert frob(host(grad), want_G) <= 1e-5
+
+
 def random_stack(seed):
     """A seeded stack of four layers whose (T, d, p) are drawn so that the sweep reaches every
     16-bit kernel: whole and ragged k-blocks, widths from 8 up, both norm paths."""
