@@ -12,6 +12,8 @@ timed with events around its launches inside the timed loop) and the CPU oracle 
 sample of the same workload.  `per_config` holds the same measurements for cfg1, cfg2 and cfg3
 taken in the same process, and `noise_pass` the separate noise pass (dp_add_noise) on cfg4's
 shard and on cfg2's whole gradient, as bytes moved per second against the HBM peak.
+`ms_per_step_without_stage_events` repeats the K timed steps without the four event records per
+step that the stage times need (they cost a fifth of a step on the smallest workload).
 """
 from __future__ import annotations
 
@@ -192,6 +194,14 @@ def measure(name, args, torch, BkPipeline, noise_pass=False):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # The same K steps once more without the per-stage event records: on the small workloads the
+    # four records per step cost more than the launches they separate.
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t0) * 1e3 / args.steps
+
     stage = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(4)] for e in events])   # ms
     ms_norm, ms_clip, ms_grad, ms_noise = stage.mean(axis=0)
     ms_step = elapsed * 1e3 / args.steps
@@ -210,6 +220,8 @@ def measure(name, args, torch, BkPipeline, noise_pass=False):
         "ms_per_step": ms_step,
         "samples_per_s": w.B / (ms_step * 1e-3),
         "ms_per_step_events": {"median": float(np.median(per_step)), "min": float(per_step.min())},
+        "ms_per_step_without_stage_events": ms_plain,
+        "samples_per_s_without_stage_events": w.B / (ms_plain * 1e-3),
         "stage_ms": {"norms": float(ms_norm), "clip": float(ms_clip), "grad": float(ms_grad), "noise": float(ms_noise)},
         # executed = what the kernels issue (the ghost-norm kernel skips the lower triangle of the
         # symmetric Gram matrices); model = the paper's operation counts (complexity table, section 3)
@@ -340,6 +352,7 @@ def main():
         "stage_ms": head["stage_ms"],
         "norm_stage": head["norm_stage"],
         "ms_per_step_events": head["ms_per_step_events"],
+        "ms_per_step_without_stage_events": head["ms_per_step_without_stage_events"],
         "seeds": {"data": w.data_seed, "noise": w.noise_seed, "noise_step": w.noise_step},
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "clock_mhz": (getattr(props, "clock_rate", 0) or 0) / 1e3 or None,
