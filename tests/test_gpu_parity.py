@@ -501,6 +501,13 @@ def test_random_stacks(dp, Pipe, seed, dtype):
         Cg = host(pipe.C).astype(np.float64)
         for l, (a, g) in enumerate(l64):
             assert frob(host(pipe.grads[l]), o.clipped_grad(a, g, Cg)) <= 1e-5, (l, B, Ts, dims)
+        # no atomics anywhere: the same call gives the same bits
+        first = pipe.flat.clone()
+        sq_first = pipe.sqnorm.clone()
+        pipe.norms()
+        pipe.flat.fill_(-1.0)
+        pipe.grad()
+        assert torch.equal(pipe.flat, first) and torch.equal(pipe.sqnorm, sq_first)
         # noise in the gradient pass = gradient pass + noise pass, on a shard inside the stack
         lo, cnt = pipe.psi // 7, pipe.psi // 2
         two_pass = pipe.flat.clone()
